@@ -1,0 +1,183 @@
+/*
+ * btx_moe.h - C ABI of the MI355X (gfx950) Mixture-of-Experts feed-forward layer
+ * of Branch-Train-MiX (arXiv 2403.07816).
+ *
+ * The layer (Sec. 3.2):   FF_MoE(x) = sum_i g_i(W_l x) * FF_i(x)
+ * with a linear router W_l, a sparse routing function g, and per-expert SwiGLU
+ * feed-forward sublayers FF_i(x) = (silu(x W1_i) * (x W3_i)) W2_i taken from the
+ * branched expert models.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless the comment says "host".
+ *   - Tensors are row-major and contiguous.  T = tokens, d = model width,
+ *     f = feed-forward width per expert, E = experts, k = experts per token,
+ *     R = T*k routed rows.
+ *   - The caller owns every buffer, including the workspace; the library
+ *     allocates nothing and keeps no state between calls.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.  Group sizes
+ *     never travel to the host.
+ *   - The return value is a btx_status.  Nothing throws, aborts or prints.
+ *     Arguments are validated before anything is launched; on an error status
+ *     no kernel has been enqueued.
+ *   - T == 0 is a valid no-op (BTX_OK).
+ *   - Every kernel is free of atomics: results are bit-identical run to run.
+ *   - Outputs must not alias inputs unless stated.  NaN/Inf inputs give
+ *     unspecified results.
+ */
+#ifndef BTX_MOE_H
+#define BTX_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BTX_OK = 0,
+  BTX_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad enum, k > E, ...            */
+  BTX_ERR_UNSUPPORTED = 2, /* valid by the paper but outside what the kernels accept  */
+  BTX_ERR_WORKSPACE = 3,   /* workspace smaller than the matching *_workspace_bytes() */
+  BTX_ERR_HIP = 4          /* a HIP launch reported an error                          */
+} btx_status;
+
+typedef enum {
+  BTX_F32 = 0, /* float                                    */
+  BTX_BF16 = 1 /* bfloat16 storage, fp32 accumulation      */
+} btx_dtype;
+
+/* Routing function g (Sec. 3.2 and Sec. 3.3 "Routing method"). */
+typedef enum {
+  /* Top-k: keep the k largest logits, softmax over the kept ones (equal to the
+   * full softmax renormalised over the chosen k).  Gates sum to 1 per token. */
+  BTX_ROUTE_TOPK_RENORM = 0,
+  /* Switch: k = 1, expert = argmax, gate = that expert's full-softmax probability. */
+  BTX_ROUTE_SWITCH_TOP1 = 1,
+  /* Sample top-1: k = 1, expert = first e with cumsum_{j<=e} softmax_j > U[t]
+   * (E-1 if none), gate = that expert's full-softmax probability. */
+  BTX_ROUTE_SAMPLE_TOP1 = 2
+} btx_route_mode;
+
+/* u_i of the load-balancing loss L_LB = alpha * E * sum_i u_i p_i (Sec. 3.3),
+ * p_i = batch mean of softmax_i. */
+typedef enum {
+  BTX_LB_TOKEN_FRAC = 0, /* u_i = counts_i / (T*k): share of routed (token,slot) pairs */
+  BTX_LB_GATE_MEAN = 1   /* u_i = (sum_t g_i) / T: the formula as printed              */
+} btx_lb_mode;
+
+/* btx_moe_ff_backward flags */
+#define BTX_FLAG_LB_GRAD_THROUGH_U 1u /* BTX_LB_GATE_MEAN only: also differentiate u_i */
+
+const char* btx_status_string(int status);
+int btx_version(void);
+
+/* ---------------------------------------------------------------------------
+ * btx_moe_route - router linear, softmax, selection, gates, load-balancing
+ * statistics and the token -> expert grouping (Sec. 3.2: W_l x and
+ * g = SoftMax(TopK(.)); Sec. 3.3: load balancing, Switch, sample top-1; the
+ * grouping is what "skip FF_i where the gate is zero" needs).
+ *
+ *   x          [T,d]   x_dtype (BTX_F32 or BTX_BF16)
+ *   W_router   [d,E]   fp32
+ *   b_router   [E]     fp32, may be NULL (the paper's router has no bias)
+ *   U          [T]     fp32 in [0,1); required iff route_mode == SAMPLE_TOP1
+ * Selection: logits are accumulated in fp32; ties go to the lower expert index;
+ * topk_idx lists the chosen experts by descending logit.
+ * Outputs
+ *   topk_idx   [T,k]   int32 expert ids
+ *   gates      [T,k]   fp32
+ *   probs      [T,E]   fp32 full softmax (kept for the backward pass)
+ *   counts     [E]     int32 routed rows per expert
+ *   offsets    [E+1]   int32 exclusive prefix of counts
+ *   perm       [R]     int32: perm[r] = t*k+j of the pair stored at grouped row r;
+ *                      rows of expert e are offsets[e]..offsets[e+1]-1, in (t,j) order
+ *   inv_pos    [T,k]   int32: inverse of perm
+ *   gate_sum   [E]     fp32 sum_t g_{t,e}
+ *   prob_sum   [E]     fp32 sum_t softmax_{t,e}
+ *   lb_loss    [1]     fp32 lb_alpha * E * sum_e u_e * prob_sum_e / T
+ * Requirements: 1 <= k <= E <= 64; d % 8 == 0; SWITCH/SAMPLE need k == 1;
+ * T*k < 2^31.  workspace >= btx_moe_route_workspace_bytes(T,E,k).
+ */
+size_t btx_moe_route_workspace_bytes(int T, int E, int k);
+int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U,
+                  int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha,
+                  int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
+                  int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_moe_ff_forward - gather tokens into expert groups, the expert SwiGLU
+ * FFNs as grouped GEMMs, and the gate-weighted combine (layer equation of
+ * Sec. 3.2; FF_i is the seed model's 3-matrix feed-forward, Sec. 4.1).
+ *
+ *   x   [T,d]            dtype
+ *   W1, W3  expert e at  W + e*w13_expert_stride elements, [d,f] row-major
+ *   W2      expert e at  W2 + e*w2_expert_stride elements, [f,d] row-major
+ *   gates, offsets, perm, inv_pos: as written by btx_moe_route
+ *   out [T,d]            dtype:  out[t] = sum_j gates[t,j] * FF_{idx[t,j]}(x[t]),
+ *                        summed over j in ascending order in fp32, rounded once
+ *   save_h1, save_h3 [R,f] dtype, grouped-row order: x W1_e and x W3_e, kept for
+ *                        the backward pass.  Both NULL = forward only.
+ * dtype BTX_BF16: bf16 storage, bf16 MFMA products, fp32 accumulation; the
+ * activation silu(h1)*h3 and the expert output are rounded to bf16 once each.
+ * dtype BTX_F32: plain fp32 FMA kernels (parity path, not the fast path).
+ * Requirements: d % 8 == 0, f % 8 == 0, strides >= d*f.
+ */
+size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int dtype);
+int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,
+                       int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d, int f, int E, int k,
+                       const float* gates, const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos,
+                       void* out, void* save_h1, void* save_h3,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_moe_ff_backward - gradients of  <dY, out> + lb_grad_scale * lb_loss  with
+ * the discrete expert selection held fixed (chain rule on Sec. 3.2's layer
+ * equation and Sec. 3.3's load-balancing loss; the paper trains the layer by
+ * gradient descent but prints no backward).
+ *
+ *   dY [T,d] dtype; x, W*, strides, routing outputs, save_h1/save_h3 as in forward
+ *   lb_grad_scale: upstream gradient of lb_loss (1 when it is added to the
+ *                  training loss as in Sec. 3.3; 0 = no load-balancing gradient)
+ * Outputs (overwritten, never accumulated into)
+ *   dX        [T,d]  dtype
+ *   dW_router [d,E]  fp32
+ *   db_router [E]    fp32, may be NULL
+ *   dW1, dW3, dW2    stacked like W1/W3/W2 (same strides), dW_dtype; all three
+ *                    NULL = frozen experts (router and input gradients only).
+ *                    Experts with no routed rows get zeros.
+ * Requirements as forward; dW_dtype must equal dtype or be BTX_F32.
+ */
+size_t btx_moe_ff_backward_workspace_bytes(int T, int d, int f, int E, int k, int dtype);
+int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, const void* W1, const void* W3,
+                        const void* W2, int dtype, int64_t w13_expert_stride, int64_t w2_expert_stride,
+                        int T, int d, int f, int E, int k, int route_mode, int lb_mode, float lb_alpha,
+                        float lb_grad_scale, unsigned flags,
+                        const int32_t* topk_idx, const float* gates, const float* probs,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos,
+                        const float* gate_sum, const float* prob_sum, const int32_t* counts,
+                        const void* save_h1, const void* save_h3,
+                        void* dX, float* dW_router, float* db_router, void* dW1, void* dW3, void* dW2,
+                        int dW_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_merge_average - elementwise mean of N same-shape tensors: how the
+ * non-feed-forward parameters (attention, embeddings, ...) of the branched
+ * models are merged (Sec. 3.2).
+ *
+ *   inputs  HOST array of N device pointers, each [numel] of dtype
+ *   out     [numel] dtype; may alias any inputs[i]
+ * BTX_BF16: the sum is taken in fp32 in input order and its quotient by N is
+ * rounded to bf16 once (no double rounding through fp32).  BTX_F32: sum and
+ * division in fp64, rounded once to fp32.  The mean of N equal tensors is
+ * that tensor, bit for bit.
+ * Requirements: 1 <= N <= 16, numel >= 0, pointers aligned to 16 bytes.
+ */
+int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BTX_MOE_H */

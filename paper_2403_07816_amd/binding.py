@@ -1,0 +1,224 @@
+"""ctypes binding of libbtx_moe.so: same names as the C ABI (include/btx_moe.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the layer runs in the library's kernels.  There is no
+fallback: if the shared library is missing, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+BTX_F32, BTX_BF16 = 0, 1
+BTX_ROUTE_TOPK_RENORM, BTX_ROUTE_SWITCH_TOP1, BTX_ROUTE_SAMPLE_TOP1 = 0, 1, 2
+BTX_LB_TOKEN_FRAC, BTX_LB_GATE_MEAN = 0, 1
+BTX_FLAG_LB_GRAD_THROUGH_U = 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbtx_moe.so")
+_lib = None
+
+_vp, _i, _i64, _f, _sz, _u = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t,
+                              ctypes.c_uint)
+_SIGNATURES = {
+    "btx_status_string": (ctypes.c_char_p, [_i]),
+    "btx_version": (_i, []),
+    "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
+    "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
+    "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),
+    "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 3 +
+                           [_vp, _sz, _vp]),
+    "btx_moe_ff_backward_workspace_bytes": (_sz, [_i] * 6),
+    "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u] + [_vp] * 11 + [_vp] * 6 +
+                            [_i, _vp, _sz, _vp]),
+    "btx_merge_average": (_i, [ctypes.POINTER(_vp), _i, _vp, _i64, _i, _vp]),
+}
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_07816_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+class BtxError(RuntimeError):
+    pass
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise BtxError(f"{what}: {load_library().btx_status_string(status).decode()} (status {status})")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return BTX_F32
+    if t.dtype == torch.bfloat16:
+        return BTX_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
+    if workspace is not None and workspace.numel() * workspace.element_size() >= nbytes:
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Routing:
+    topk_idx: torch.Tensor   # [T,k] int32
+    gates: torch.Tensor      # [T,k] fp32
+    probs: torch.Tensor      # [T,E] fp32
+    counts: torch.Tensor     # [E] int32
+    offsets: torch.Tensor    # [E+1] int32
+    perm: torch.Tensor       # [T*k] int32
+    inv_pos: torch.Tensor    # [T,k] int32
+    gate_sum: torch.Tensor   # [E] fp32
+    prob_sum: torch.Tensor   # [E] fp32
+    lb_loss: torch.Tensor    # [1] fp32
+
+
+def alloc_routing(T: int, E: int, k: int, device) -> Routing:
+    i32 = dict(dtype=torch.int32, device=device)
+    f32 = dict(dtype=torch.float32, device=device)
+    return Routing(torch.empty((T, k), **i32), torch.empty((T, k), **f32), torch.empty((T, E), **f32),
+                   torch.zeros(E, **i32), torch.zeros(E + 1, **i32), torch.empty(T * k, **i32),
+                   torch.empty((T, k), **i32), torch.zeros(E, **f32), torch.zeros(E, **f32), torch.zeros(1, **f32))
+
+
+def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[torch.Tensor] = None,
+                  U: Optional[torch.Tensor] = None, k: int = 2, route_mode: int = BTX_ROUTE_TOPK_RENORM,
+                  lb_mode: int = BTX_LB_TOKEN_FRAC, lb_alpha: float = 0.0, out: Optional[Routing] = None,
+                  workspace: Optional[torch.Tensor] = None) -> Routing:
+    lib = load_library()
+    T, d = x.shape
+    E = W_router.shape[1]
+    assert W_router.shape[0] == d and W_router.dtype == torch.float32
+    r = out if out is not None else alloc_routing(T, E, k, x.device)
+    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), x.device, workspace)
+    st = lib.btx_moe_route(_ptr(x), _dtype_code(x), _ptr(W_router), _ptr(b_router), _ptr(U), T, d, E, k, route_mode,
+                           lb_mode, lb_alpha, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
+                           _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum),
+                           _ptr(r.lb_loss), _ptr(ws), ws.numel(), _stream())
+    _check(st, "btx_moe_route")
+    return r
+
+
+def _stacked(W: torch.Tensor) -> Tuple[int, int]:
+    assert W.dim() == 3 and W.is_contiguous()
+    return W.shape[0], W.stride(0)
+
+
+def btx_moe_ff_forward(x: torch.Tensor, W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, routing: Routing,
+                       save: bool = True, out: Optional[torch.Tensor] = None,
+                       saved: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+                       workspace: Optional[torch.Tensor] = None):
+    """Returns (out[T,d], h1, h3); h1/h3 are None when save=False."""
+    lib = load_library()
+    T, d = x.shape
+    E, s13 = _stacked(W1)
+    _, s2 = _stacked(W2)
+    f = W1.shape[2]
+    k = routing.topk_idx.shape[1]
+    dt = _dtype_code(x)
+    assert W1.dtype == x.dtype and W3.shape == W1.shape and W2.shape == (E, f, d)
+    out = out if out is not None else torch.empty_like(x)
+    h1 = h3 = None
+    if save:
+        h1, h3 = saved if saved is not None else (torch.empty((T * k, f), dtype=x.dtype, device=x.device),
+                                                  torch.empty((T * k, f), dtype=x.dtype, device=x.device))
+    ws = _workspace(lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
+    st = lib.btx_moe_ff_forward(_ptr(x), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f, E, k,
+                                _ptr(routing.gates), _ptr(routing.offsets), _ptr(routing.perm), _ptr(routing.inv_pos),
+                                _ptr(out), _ptr(h1), _ptr(h3), _ptr(ws), ws.numel(), _stream())
+    _check(st, "btx_moe_ff_forward")
+    return out, h1, h3
+
+
+@dataclass
+class Grads:
+    dX: torch.Tensor
+    dW_router: torch.Tensor
+    db_router: torch.Tensor
+    dW1: Optional[torch.Tensor]
+    dW3: Optional[torch.Tensor]
+    dW2: Optional[torch.Tensor]
+
+
+def btx_moe_ff_backward(dY: torch.Tensor, x: torch.Tensor, W_router: torch.Tensor, W1: torch.Tensor,
+                        W3: torch.Tensor, W2: torch.Tensor, routing: Routing, h1: torch.Tensor, h3: torch.Tensor,
+                        route_mode: int = BTX_ROUTE_TOPK_RENORM, lb_mode: int = BTX_LB_TOKEN_FRAC,
+                        lb_alpha: float = 0.0, lb_grad_scale: float = 0.0, flags: int = 0,
+                        dW_dtype: Optional[torch.dtype] = None, frozen_experts: bool = False,
+                        out: Optional[Grads] = None, workspace: Optional[torch.Tensor] = None) -> Grads:
+    lib = load_library()
+    T, d = x.shape
+    E, s13 = _stacked(W1)
+    _, s2 = _stacked(W2)
+    f = W1.shape[2]
+    k = routing.topk_idx.shape[1]
+    dt = _dtype_code(x)
+    dW_dtype = x.dtype if dW_dtype is None else dW_dtype
+    if out is None:
+        mk = (lambda W: None) if frozen_experts else (lambda W: torch.empty(W.shape, dtype=dW_dtype, device=x.device))
+        out = Grads(torch.empty_like(x), torch.empty((d, W_router.shape[1]), dtype=torch.float32, device=x.device),
+                    torch.empty(W_router.shape[1], dtype=torch.float32, device=x.device), mk(W1), mk(W3), mk(W2))
+    dwc = BTX_F32 if dW_dtype == torch.float32 else BTX_BF16
+    ws = _workspace(lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
+    st = lib.btx_moe_ff_backward(_ptr(dY), _ptr(x), _ptr(W_router), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f,
+                                 E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, _ptr(routing.topk_idx),
+                                 _ptr(routing.gates), _ptr(routing.probs), _ptr(routing.offsets), _ptr(routing.perm),
+                                 _ptr(routing.inv_pos), _ptr(routing.gate_sum), _ptr(routing.prob_sum),
+                                 _ptr(routing.counts), _ptr(h1), _ptr(h3), _ptr(out.dX), _ptr(out.dW_router),
+                                 _ptr(out.db_router), _ptr(out.dW1), _ptr(out.dW3), _ptr(out.dW2), dwc, _ptr(ws),
+                                 ws.numel(), _stream())
+    _check(st, "btx_moe_ff_backward")
+    return out
+
+
+def btx_merge_average(tensors: Sequence[torch.Tensor], out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    lib = load_library()
+    t0 = tensors[0]
+    for t in tensors:
+        assert t.shape == t0.shape and t.dtype == t0.dtype and t.is_cuda and t.is_contiguous()
+    out = out if out is not None else torch.empty_like(t0)
+    arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+    st = lib.btx_merge_average(arr, len(tensors), _ptr(out), t0.numel(), _dtype_code(t0), _stream())
+    _check(st, "btx_merge_average")
+    return out
+
+
+def split_experts(W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, C: int):
+    """Re-index stacked experts [N,d,f] / [N,f,d] into N*C experts of width f/C
+    (Sec. 3.3 "Splitting Experts"): expert i*C+c owns columns c*f/C.. of W1_i, W3_i
+    and the same rows of W2_i.  A one-off layout copy made when the MoE is built."""
+    N, d, f = W1.shape
+    assert f % C == 0
+    fc = f // C
+    s1 = W1.reshape(N, d, C, fc).permute(0, 2, 1, 3).reshape(N * C, d, fc).contiguous()
+    s3 = W3.reshape(N, d, C, fc).permute(0, 2, 1, 3).reshape(N * C, d, fc).contiguous()
+    s2 = W2.reshape(N * C, fc, d).contiguous()
+    return s1, s3, s2

@@ -1,0 +1,189 @@
+// C ABI of the library: argument validation, workspace carving, and the order in which
+// the stages of the layer are enqueued.  See include/btx_moe.h for the contract.
+#include "common.h"
+
+using namespace btx;
+
+namespace {
+
+struct Carver {
+  char* base; size_t used;
+  explicit Carver(void* p) : base(static_cast<char*>(p)), used(0) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + used : nullptr;
+    used += align_up(bytes, 256);
+    return p;
+  }
+};
+
+inline int esize(int dtype) { return dtype == BTX_BF16 ? 2 : 4; }
+inline bool dtype_ok(int dtype) { return dtype == BTX_F32 || dtype == BTX_BF16; }
+
+struct FwdWs { void *xs, *act, *y, *h1, *h3; size_t bytes; };
+FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype) {
+  const size_t R = (size_t)T * k, es = esize(dtype);
+  Carver c(ws);
+  FwdWs w;
+  w.xs = c.take(R * d * es);
+  w.act = c.take(R * f * es);
+  w.y = c.take(R * d * es);
+  w.h1 = c.take(R * f * es);  // used only when the caller does not keep h1/h3
+  w.h3 = c.take(R * f * es);
+  w.bytes = c.used;
+  return w;
+}
+
+struct BwdWs { void *xs, *dys, *dh1, *dh3, *ga, *dxs, *scratch, *router; float* dg_part; size_t bytes; };
+BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
+  const size_t R = (size_t)T * k, es = esize(dtype);
+  Carver c(ws);
+  BwdWs w;
+  w.xs = c.take(R * d * es);
+  w.dys = c.take(R * d * es);
+  w.dh1 = c.take(R * f * es);
+  w.dh3 = c.take(R * f * es);
+  w.ga = c.take(R * f * es);
+  w.dxs = c.take(R * d * es);
+  w.dg_part = static_cast<float*>(c.take(R * (size_t)bwd_act_partials(dtype, f) * sizeof(float)));
+  w.scratch = c.take(ff_scratch_bytes(dtype, (int)R, f));
+  w.router = c.take(router_bwd_workspace_bytes(T, d, E));
+  w.bytes = c.used;
+  return w;
+}
+
+bool shapes_ok(int T, int d, int f, int E, int k) {
+  return T >= 0 && d > 0 && f > 0 && E >= 1 && E <= kMaxExperts && k >= 1 && k <= E && d % 8 == 0 && f % 8 == 0 &&
+         (int64_t)T * k < (int64_t)1 << 31 && (int64_t)T * k * (int64_t)(d > f ? d : f) < (int64_t)1 << 40;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* btx_status_string(int status) {
+  switch (status) {
+    case BTX_OK: return "ok";
+    case BTX_ERR_INVALID_ARG: return "invalid argument";
+    case BTX_ERR_UNSUPPORTED: return "unsupported configuration";
+    case BTX_ERR_WORKSPACE: return "workspace too small";
+    case BTX_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int btx_version(void) { return 1; }
+
+size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
+  if (T <= 0 || E < 1 || E > kMaxExperts || k < 1 || k > E) return 0;
+  return route_workspace_bytes(T, E, k);
+}
+
+int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T, int d,
+                  int E, int k, int route_mode, int lb_mode, float lb_alpha, int32_t* topk_idx, float* gates,
+                  float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
+                  float* prob_sum, float* lb_loss, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(x_dtype) || T < 0 || d <= 0 || d % 8 != 0 || E < 1 || E > kMaxExperts || k < 1 || k > E)
+    return BTX_ERR_INVALID_ARG;
+  if ((int64_t)T * k >= (int64_t)1 << 31) return BTX_ERR_INVALID_ARG;
+  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_SAMPLE_TOP1) return BTX_ERR_INVALID_ARG;
+  if (lb_mode != BTX_LB_TOKEN_FRAC && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
+  if (route_mode != BTX_ROUTE_TOPK_RENORM && k != 1) return BTX_ERR_INVALID_ARG;
+  if ((route_mode == BTX_ROUTE_SAMPLE_TOP1) != (U != nullptr)) return BTX_ERR_INVALID_ARG;
+  if (T == 0) return BTX_OK;
+  if (!x || !W_router || !topk_idx || !gates || !probs || !counts || !offsets || !perm || !inv_pos || !gate_sum ||
+      !prob_sum || !lb_loss || !workspace)
+    return BTX_ERR_INVALID_ARG;
+  if (workspace_bytes < route_workspace_bytes(T, E, k)) return BTX_ERR_WORKSPACE;
+  RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, topk_idx, gates, probs,
+              counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace};
+  return launch_route(a, static_cast<hipStream_t>(stream));
+}
+
+size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int dtype) {
+  if (!dtype_ok(dtype) || !shapes_ok(T, d, f, E, k) || T == 0) return 0;
+  return carve_forward(nullptr, T, d, f, k, dtype).bytes;
+}
+
+int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,
+                       int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d, int f, int E, int k,
+                       const float* gates, const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos, void* out,
+                       void* save_h1, void* save_h3, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dtype) || !shapes_ok(T, d, f, E, k)) return BTX_ERR_INVALID_ARG;
+  if (w13_expert_stride < (int64_t)d * f || w2_expert_stride < (int64_t)d * f) return BTX_ERR_INVALID_ARG;
+  if ((save_h1 == nullptr) != (save_h3 == nullptr)) return BTX_ERR_INVALID_ARG;
+  if (T == 0) return BTX_OK;
+  if (!x || !W1 || !W3 || !W2 || !gates || !offsets || !perm || !inv_pos || !out || !workspace)
+    return BTX_ERR_INVALID_ARG;
+  const FwdWs w = carve_forward(workspace, T, d, f, k, dtype);
+  if (workspace_bytes < w.bytes) return BTX_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int R = T * k;
+  const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
+  void* h1 = save_h1 ? save_h1 : w.h1;
+  void* h3 = save_h3 ? save_h3 : w.h3;
+  if (int rc = launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s)) return rc;
+  if (int rc = launch_up_swiglu(dtype, w.xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s)) return rc;
+  if (int rc = launch_down(dtype, w.act, W2, offsets, sh, w.y, s)) return rc;
+  return launch_combine(w.y, gates, inv_pos, out, T, k, d, dtype, s);
+}
+
+size_t btx_moe_ff_backward_workspace_bytes(int T, int d, int f, int E, int k, int dtype) {
+  if (!dtype_ok(dtype) || !shapes_ok(T, d, f, E, k) || T == 0) return 0;
+  return carve_backward(nullptr, T, d, f, E, k, dtype).bytes;
+}
+
+int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, const void* W1, const void* W3,
+                        const void* W2, int dtype, int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d,
+                        int f, int E, int k, int route_mode, int lb_mode, float lb_alpha, float lb_grad_scale,
+                        unsigned flags, const int32_t* topk_idx, const float* gates, const float* probs,
+                        const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos, const float* gate_sum,
+                        const float* prob_sum, const int32_t* counts, const void* save_h1, const void* save_h3, void* dX,
+                        float* dW_router, float* db_router, void* dW1, void* dW3, void* dW2, int dW_dtype,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dtype) || !dtype_ok(dW_dtype) || !shapes_ok(T, d, f, E, k)) return BTX_ERR_INVALID_ARG;
+  if (dW_dtype != dtype && dW_dtype != BTX_F32) return BTX_ERR_INVALID_ARG;
+  if (w13_expert_stride < (int64_t)d * f || w2_expert_stride < (int64_t)d * f) return BTX_ERR_INVALID_ARG;
+  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_SAMPLE_TOP1) return BTX_ERR_INVALID_ARG;
+  if (route_mode != BTX_ROUTE_TOPK_RENORM && k != 1) return BTX_ERR_INVALID_ARG;
+  if (lb_mode != BTX_LB_TOKEN_FRAC && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
+  if (flags & ~BTX_FLAG_LB_GRAD_THROUGH_U) return BTX_ERR_INVALID_ARG;
+  if ((flags & BTX_FLAG_LB_GRAD_THROUGH_U) && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
+  const int n_dw = (dW1 != nullptr) + (dW3 != nullptr) + (dW2 != nullptr);
+  if (n_dw != 0 && n_dw != 3) return BTX_ERR_INVALID_ARG;
+  if (T == 0) return BTX_OK;
+  if (!dY || !x || !W_router || !W1 || !W3 || !W2 || !topk_idx || !gates || !probs || !offsets || !perm || !inv_pos ||
+      !gate_sum || !prob_sum || !counts || !save_h1 || !save_h3 || !dX || !dW_router || !workspace)
+    return BTX_ERR_INVALID_ARG;
+  const BwdWs w = carve_backward(workspace, T, d, f, E, k, dtype);
+  if (workspace_bytes < w.bytes) return BTX_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int R = T * k;
+  const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
+  if (int rc = launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s)) return rc;
+  if (int rc = launch_bwd_act(dtype, w.dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1, w.dh3, w.ga,
+                              w.dg_part, w.scratch, s))
+    return rc;
+  if (int rc = launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s)) return rc;
+  if (n_dw == 3) {
+    if (int rc = launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s)) return rc;
+    if (int rc = launch_bwd_dw(dtype, dW_dtype, w.xs, w.dh1, w.dh3, w.ga, w.dys, offsets, sh, dW1, dW3, dW2, s))
+      return rc;
+  }
+  RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, topk_idx,
+                   gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,
+                   dW_router, db_router, w.router};
+  return launch_router_bwd(ra, s);
+}
+
+int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, void* stream) {
+  if (!dtype_ok(dtype) || N < 1 || N > 16 || numel < 0 || !inputs) return BTX_ERR_INVALID_ARG;
+  if (numel == 0) return BTX_OK;
+  if (!out || ((uintptr_t)out & 15)) return BTX_ERR_INVALID_ARG;
+  for (int n = 0; n < N; ++n)
+    if (!inputs[n] || ((uintptr_t)inputs[n] & 15)) return BTX_ERR_INVALID_ARG;
+  return launch_merge_average(inputs, N, out, numel, dtype, static_cast<hipStream_t>(stream));
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

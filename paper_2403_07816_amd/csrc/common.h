@@ -1,0 +1,132 @@
+// Shared device/host helpers of the gfx950 MoE feed-forward library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "btx_moe.h"
+
+namespace btx {
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 64;
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Round to nearest even; inputs are finite by contract.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Which expert owns grouped row-tile `tile` when every expert's rows are cut
+// into tiles of BM rows, experts laid one after another.  Returns false past
+// the last tile.  offsets has E+1 entries.
+__device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ offsets, int E, int BM, int tile,
+                                               int& expert, int& row0, int& row_end) {
+  int t = tile;
+  for (int e = 0; e < E; ++e) {
+    const int b = offsets[e], n = offsets[e + 1] - b;
+    const int nt = (n + BM - 1) / BM;
+    if (t < nt) {
+      expert = e;
+      row0 = b + t * BM;
+      row_end = b + n;
+      return true;
+    }
+    t -= nt;
+  }
+  return false;
+}
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define BTX_LAUNCH_CHECK()                                   \
+  do {                                                       \
+    if (hipGetLastError() != hipSuccess) return BTX_ERR_HIP; \
+  } while (0)
+
+// ---- internal launchers (one translation unit each) ------------------------
+struct RouteArgs {
+  const void* x; int x_dtype; const float* W_router; const float* b_router; const float* U;
+  int T, d, E, k, route_mode, lb_mode; float lb_alpha;
+  int32_t* topk_idx; float* gates; float* probs; int32_t* counts; int32_t* offsets; int32_t* perm;
+  int32_t* inv_pos; float* gate_sum; float* prob_sum; float* lb_loss;
+  void* workspace;
+};
+size_t route_workspace_bytes(int T, int E, int k);
+int launch_route(const RouteArgs& a, hipStream_t s);
+
+// rows: dst[r] = src[perm[r] / k]  (k = 1 with perm = NULL copies nothing; perm required)
+int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, int k, int d, int dtype, hipStream_t s);
+// out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]   (gates NULL => unit weights)
+int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d,
+                   int dtype, hipStream_t s);
+
+// Expert GEMM stages.  `offsets` = E+1 grouped-row offsets on the device.
+struct FfShapes { int R, d, f, E; int64_t s13, s2; };
+// a = silu(xs W1) * (xs W3); h1/h3 stored when non-null
+int launch_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* offsets,
+                     const FfShapes& sh, void* h1, void* h3, void* act, void* scratch, hipStream_t s);
+// y = act W2
+int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
+                hipStream_t s);
+// D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a
+int bwd_act_partials(int dtype, int f);
+int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+                   const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
+                   float* dg_part, void* scratch, hipStream_t s);
+// dxs = dh1 W1^T + dh3 W3^T
+int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
+                  const FfShapes& sh, void* dxs, hipStream_t s);
+// dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows
+int launch_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
+                  const void* dys, const int32_t* offsets, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
+                  hipStream_t s);
+size_t ff_scratch_bytes(int dtype, int R, int f);
+
+struct RouterBwdArgs {
+  const void* x; int dtype; const float* W_router; int T, d, E, k, route_mode, lb_mode; float lb_alpha, lb_grad_scale;
+  unsigned flags; const int32_t* topk_idx; const float* gates; const float* probs; const int32_t* inv_pos;
+  const float* gate_sum; const float* prob_sum; const int32_t* counts; const float* dg_part; int n_part;
+  const void* dxs; void* dX; float* dW_router; float* db_router; void* workspace;
+};
+size_t router_bwd_workspace_bytes(int T, int d, int E);
+int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s);
+
+int launch_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, hipStream_t s);
+
+}  // namespace btx

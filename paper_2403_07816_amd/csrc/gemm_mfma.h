@@ -1,0 +1,17 @@
+// Entry points of the bf16 MFMA grouped-GEMM path (see gemm_mfma.hip).
+#pragma once
+#include "common.h"
+
+namespace btx {
+int mfma_bwd_act_partials(int f);
+int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* h1,
+                   void* h3, void* act, hipStream_t s);
+int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s);
+int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+                 const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* ga,
+                 float* dg_part, hipStream_t s);
+int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
+                const FfShapes& sh, void* dxs, hipStream_t s);
+int mfma_bwd_dw(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga, const void* dys,
+                const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2, hipStream_t s);
+}  // namespace btx

@@ -1,0 +1,106 @@
+// Row movement around the expert GEMMs (both HBM-bound streaming kernels):
+//   gather_rows  dst[r] = src[perm[r] / k]: token rows copied into expert-grouped order
+//                (forward: x -> xs; backward: dY -> dys).
+//   combine      out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]: the gate-weighted sum of the
+//                layer equation (Sec. 3.2), one wavefront per token row, slots summed in
+//                ascending j in fp32, one rounding.  No atomics: every output row has
+//                exactly one writer.
+// Rows are moved as 16-byte chunks, consecutive lanes on consecutive chunks.
+#include "common.h"
+
+namespace btx {
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                               const int32_t* __restrict__ perm, int R, int k,
+                                                               int chunks_per_row) {
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  const int r = blockIdx.x * (kThreads / kWave) + wave;
+  if (r >= R) return;
+  const int t = perm[r] / k;
+  const u32x4* s = src + (size_t)t * chunks_per_row;
+  u32x4* o = dst + (size_t)r * chunks_per_row;
+  for (int c = lane; c < chunks_per_row; c += kWave) o[c] = s[c];
+}
+
+template <typename ET> struct Chunk;  // 16 bytes of elements <-> floats
+template <> struct Chunk<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const u32x4& w, float* v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* v) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+    return w;
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& w, float* v) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(w[i]);
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* v) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = __float_as_uint(v[i]);
+    return w;
+  }
+};
+
+template <typename ET>
+__global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restrict__ y, const float* __restrict__ gates,
+                                                           const int32_t* __restrict__ inv_pos, u32x4* __restrict__ out,
+                                                           int T, int k, int chunks_per_row) {
+  constexpr int N = Chunk<ET>::N;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  const int t = blockIdx.x * (kThreads / kWave) + wave;
+  if (t >= T) return;
+  for (int c = lane; c < chunks_per_row; c += kWave) {
+    float acc[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    for (int j = 0; j < k; ++j) {
+      const int r = inv_pos[(size_t)t * k + j];
+      const float g = gates ? gates[(size_t)t * k + j] : 1.f;
+      float v[N];
+      Chunk<ET>::unpack(y[(size_t)r * chunks_per_row + c], v);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = fmaf(g, v[i], acc[i]);
+    }
+    out[(size_t)t * chunks_per_row + c] = Chunk<ET>::pack(acc);
+  }
+}
+
+}  // namespace
+
+int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, int k, int d, int dtype, hipStream_t s) {
+  const int esz = dtype == BTX_BF16 ? 2 : 4;
+  const int chunks = d * esz / 16;
+  gather_rows_kernel<<<ceil_div(R, kThreads / kWave), kThreads, 0, s>>>(
+      static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), perm, R, k, chunks);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d, int dtype,
+                   hipStream_t s) {
+  const int esz = dtype == BTX_BF16 ? 2 : 4;
+  const int chunks = d * esz / 16;
+  dim3 grid(ceil_div(T, kThreads / kWave));
+  if (dtype == BTX_BF16)
+    combine_kernel<bf16_t><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
+                                                     static_cast<u32x4*>(out), T, k, chunks);
+  else
+    combine_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
+                                                    static_cast<u32x4*>(out), T, k, chunks);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+}  // namespace btx

@@ -1,0 +1,339 @@
+// Router: logits, softmax, expert selection, gates, load-balancing statistics and
+// the stable grouping of (token, slot) pairs by expert (Sec. 3.2 router and Top-k;
+// Sec. 3.3 load balancing, Switch and sample-top-1 routing).
+//
+// Three launches, no atomics, no host round trip:
+//   1. route_tokens   one wavefront handles kTokPerWave tokens at a time: fp32 dot
+//                     products of the token row with W_router (lanes split the row,
+//                     butterfly reduction), then softmax / selection / gates with one
+//                     lane per expert.  Each workgroup owns kTokPerBlock consecutive
+//                     tokens and writes its per-expert counts and gate/prob sums.
+//   2. route_scan     one workgroup: per-expert exclusive scan of the block counts
+//                     (fixed order), expert offsets, finished statistics and lb_loss.
+//   3. route_scatter  one wavefront per block re-reads its indices and writes perm and
+//                     inv_pos; ranks inside a block come from wavefront ballots, so the
+//                     order inside every expert group is the (token, slot) order.
+#include "common.h"
+
+namespace btx {
+namespace {
+
+constexpr int kTokPerWave = 4;
+constexpr int kWavesPerBlock = 4;
+constexpr int kTokPerBlock = kTokPerWave * kWavesPerBlock;  // 16 consecutive tokens per workgroup
+constexpr int kScanThreads = 1024;
+
+template <typename XT> struct RowLoad;
+template <> struct RowLoad<bf16_t> {
+  static __device__ __forceinline__ void ld8(const bf16_t* p, float* v) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
+  }
+};
+template <> struct RowLoad<float> {
+  static __device__ __forceinline__ void ld8(const float* p, float* v) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+};
+
+struct Best { float v; int i; };
+// larger value wins; equal values: lower index wins
+__device__ __forceinline__ Best best_of(Best a, Best b) {
+  return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+__device__ __forceinline__ Best wave_best(Best x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    Best y{__shfl_xor(x.v, o, kWave), __shfl_xor(x.i, o, kWave)};
+    x = best_of(x, y);
+  }
+  return x;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_incl_scan(float v, int lane) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const float u = __shfl_up(v, o, kWave);
+    if (lane >= o) v += u;
+  }
+  return v;
+}
+
+// EC experts are accumulated per pass over the row; kTokPerWave tokens share each
+// W_router load.
+template <typename XT, int EC>
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
+    const XT* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ br,
+    const float* __restrict__ U, int T, int d, int E, int k, int mode, int32_t* __restrict__ topk_idx,
+    float* __restrict__ gates, float* __restrict__ probs, int32_t* __restrict__ blk_counts,
+    float* __restrict__ blk_gsum, float* __restrict__ blk_psum) {
+  __shared__ float s_logit[kWavesPerBlock][kTokPerWave][kMaxExperts];
+  __shared__ float s_stat[kWavesPerBlock][3][kMaxExperts];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int t0 = blockIdx.x * kTokPerBlock + wave * kTokPerWave;
+
+  // ---- logits -------------------------------------------------------------
+  for (int e0 = 0; e0 < E; e0 += EC) {
+    float acc[kTokPerWave][EC];
+#pragma unroll
+    for (int q = 0; q < kTokPerWave; ++q)
+#pragma unroll
+      for (int j = 0; j < EC; ++j) acc[q][j] = 0.f;
+    for (int c0 = lane * 8; c0 < d; c0 += kWave * 8) {
+      float xv[kTokPerWave][8];
+#pragma unroll
+      for (int q = 0; q < kTokPerWave; ++q) {
+        const int t = min(t0 + q, T - 1);  // clamped rows are computed and then dropped
+        RowLoad<XT>::ld8(x + (size_t)t * d + c0, xv[q]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float w[EC];
+        const float* wp = Wr + (size_t)(c0 + i) * E + e0;
+#pragma unroll
+        for (int j = 0; j < EC; ++j) w[j] = (e0 + j < E) ? wp[j] : 0.f;
+#pragma unroll
+        for (int q = 0; q < kTokPerWave; ++q)
+#pragma unroll
+          for (int j = 0; j < EC; ++j) acc[q][j] = fmaf(xv[q][i], w[j], acc[q][j]);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kTokPerWave; ++q)
+#pragma unroll
+      for (int j = 0; j < EC; ++j) {
+        const float s = wave_sum(acc[q][j]);
+        if (lane == 0 && e0 + j < E) s_logit[wave][q][e0 + j] = s;
+      }
+  }
+  __syncthreads();
+
+  // ---- per token: softmax, selection, gates; lane e owns expert e ----------
+  int cnt = 0;
+  float gsum = 0.f, psum = 0.f;
+  const bool live = lane < E;
+  for (int q = 0; q < kTokPerWave; ++q) {
+    const int t = t0 + q;
+    if (t >= T) break;  // uniform across the wave
+    const float s = live ? s_logit[wave][q][lane] + (br ? br[lane] : 0.f) : -INFINITY;
+    const float smax = wave_max(s);
+    const float z = live ? __expf(s - smax) : 0.f;
+    const float zsum = wave_sum(z);
+    const float p = z / zsum;
+    if (live) probs[(size_t)t * E + lane] = p;
+    psum += p;
+    if (mode == BTX_ROUTE_TOPK_RENORM) {
+      float cand = s;
+      int my_slot = -1;
+      for (int j = 0; j < k; ++j) {
+        const Best b = wave_best(Best{cand, lane});
+        if (lane == b.i) { my_slot = j; cand = -INFINITY; }
+      }
+      const float zsel = wave_sum(my_slot >= 0 ? z : 0.f);
+      if (my_slot >= 0) {
+        const float g = z / zsel;
+        topk_idx[(size_t)t * k + my_slot] = lane;
+        gates[(size_t)t * k + my_slot] = g;
+        gsum += g;
+        cnt += 1;
+      }
+    } else {
+      int chosen;
+      if (mode == BTX_ROUTE_SWITCH_TOP1) {
+        chosen = wave_best(Best{s, lane}).i;
+      } else {
+        const float c = wave_incl_scan(p, lane);
+        const unsigned long long m = __ballot(live && c > U[t]);
+        chosen = m ? (__ffsll((long long)m) - 1) : (E - 1);
+      }
+      if (lane == chosen) {
+        topk_idx[t] = lane;
+        gates[t] = p;
+        gsum += p;
+        cnt += 1;
+      }
+    }
+  }
+  s_stat[wave][0][lane] = __int_as_float(cnt);
+  s_stat[wave][1][lane] = gsum;
+  s_stat[wave][2][lane] = psum;
+  __syncthreads();
+  if (threadIdx.x < E) {
+    const int e = threadIdx.x;
+    int c = 0;
+    float g = 0.f, p = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      c += __float_as_int(s_stat[w][0][e]);
+      g += s_stat[w][1][e];
+      p += s_stat[w][2][e];
+    }
+    blk_counts[(size_t)blockIdx.x * E + e] = c;
+    blk_gsum[(size_t)blockIdx.x * E + e] = g;
+    blk_psum[(size_t)blockIdx.x * E + e] = p;
+  }
+}
+
+// Exclusive scan of v over the workgroup (kScanThreads threads); returns the
+// exclusive prefix and writes the total to `total`.
+__device__ __forceinline__ int block_excl_scan(int v, int& total, int* s_wave) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int u = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += u;
+  }
+  if (lane == kWave - 1) s_wave[wave] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int w = 0; w < kScanThreads / kWave; ++w) {
+    const int c = s_wave[w];
+    if (w < wave) base += c;
+    tot += c;
+  }
+  __syncthreads();
+  total = tot;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
+    int nblk, int T, int E, int k, int lb_mode, float lb_alpha, const int32_t* __restrict__ blk_counts,
+    const float* __restrict__ blk_gsum, const float* __restrict__ blk_psum, int32_t* __restrict__ blk_base,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, float* __restrict__ gate_sum,
+    float* __restrict__ prob_sum, float* __restrict__ lb_loss) {
+  __shared__ int s_wave[kScanThreads / kWave];
+  __shared__ int s_count[kMaxExperts];
+  __shared__ float s_red[2][kScanThreads / kWave];
+  __shared__ float s_g[kMaxExperts], s_p[kMaxExperts];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (int e = 0; e < E; ++e) {
+    int running = 0;
+    float g = 0.f, p = 0.f;
+    for (int b0 = 0; b0 < nblk; b0 += kScanThreads) {
+      const int b = b0 + threadIdx.x;
+      const int v = b < nblk ? blk_counts[(size_t)b * E + e] : 0;
+      int total;
+      const int ex = block_excl_scan(v, total, s_wave);
+      if (b < nblk) {
+        blk_base[(size_t)b * E + e] = running + ex;
+        g += blk_gsum[(size_t)b * E + e];
+        p += blk_psum[(size_t)b * E + e];
+      }
+      running += total;
+    }
+    // fixed-order reduction of the per-thread partial sums
+    g = wave_sum(g);
+    p = wave_sum(p);
+    if (lane == 0) { s_red[0][wave] = g; s_red[1][wave] = p; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float gs = 0.f, ps = 0.f;
+      for (int w = 0; w < kScanThreads / kWave; ++w) { gs += s_red[0][w]; ps += s_red[1][w]; }
+      s_count[e] = running;
+      s_g[e] = gs;
+      s_p[e] = ps;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    int off = 0;
+    float loss = 0.f;
+    for (int e = 0; e < E; ++e) {
+      offsets[e] = off;
+      counts[e] = s_count[e];
+      gate_sum[e] = s_g[e];
+      prob_sum[e] = s_p[e];
+      const float u = lb_mode == BTX_LB_TOKEN_FRAC ? (float)s_count[e] / ((float)T * (float)k) : s_g[e] / (float)T;
+      loss += u * (s_p[e] / (float)T);
+      off += s_count[e];
+    }
+    offsets[E] = off;
+    *lb_loss = lb_alpha * (float)E * loss;
+  }
+}
+
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void route_scatter_kernel(
+    int nblk, int T, int E, int k, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_base,
+    const int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_pos) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int b = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;  // one wavefront per token block
+  if (b >= nblk) return;
+  const int first = b * kTokPerBlock * k;
+  const int last = min((b + 1) * kTokPerBlock, T) * k;
+  // lane e carries the next free grouped row of expert e for this block
+  int next = lane < E ? offsets[lane] + blk_base[(size_t)b * E + lane] : 0;
+  for (int i0 = first; i0 < last; i0 += kWave) {
+    const int i = i0 + lane;
+    const bool valid = i < last;
+    const int e = valid ? topk_idx[i] : -1;
+    int rank = 0, base = 0;
+    for (int q = 0; q < E; ++q) {
+      const unsigned long long m = __ballot(e == q);
+      const int start = __shfl(next, q, kWave);
+      if (e == q) {
+        rank = __popcll(m & ((1ull << lane) - 1ull));
+        base = start;
+      }
+      if (lane == q) next += __popcll(m);
+    }
+    if (valid) {
+      const int pos = base + rank;
+      perm[pos] = i;
+      inv_pos[i] = pos;
+    }
+  }
+}
+
+template <typename XT>
+void launch_tokens(const RouteArgs& a, int nblk, int32_t* bc, float* bg, float* bp, hipStream_t s) {
+  const XT* x = static_cast<const XT*>(a.x);
+  dim3 grid(nblk), block(kWavesPerBlock * kWave);
+#define BTX_ROUTE_LAUNCH(EC)                                                                                  \
+  route_tokens_kernel<XT, EC><<<grid, block, 0, s>>>(x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k,      \
+                                                      a.route_mode, a.topk_idx, a.gates, a.probs, bc, bg, bp)
+  if (a.E <= 1) BTX_ROUTE_LAUNCH(1);
+  else if (a.E <= 2) BTX_ROUTE_LAUNCH(2);
+  else if (a.E <= 4) BTX_ROUTE_LAUNCH(4);
+  else BTX_ROUTE_LAUNCH(8);
+#undef BTX_ROUTE_LAUNCH
+}
+
+}  // namespace
+
+static int num_blocks(int T) { return ceil_div(T, kTokPerBlock); }
+
+size_t route_workspace_bytes(int T, int E, int /*k*/) {
+  // block counts, block bases (int32) and block gate/prob sums (fp32)
+  return align_up((size_t)num_blocks(T) * E * 4 * sizeof(int32_t), 256);
+}
+
+int launch_route(const RouteArgs& a, hipStream_t s) {
+  const int nblk = num_blocks(a.T);
+  const size_t n = (size_t)nblk * a.E;
+  int32_t* bc = static_cast<int32_t*>(a.workspace);
+  int32_t* bb = bc + n;
+  float* bg = reinterpret_cast<float*>(bb + n);
+  float* bp = bg + n;
+  if (a.x_dtype == BTX_BF16) launch_tokens<bf16_t>(a, nblk, bc, bg, bp, s);
+  else launch_tokens<float>(a, nblk, bc, bg, bp, s);
+  BTX_LAUNCH_CHECK();
+  route_scan_kernel<<<1, kScanThreads, 0, s>>>(nblk, a.T, a.E, a.k, a.lb_mode, a.lb_alpha, bc, bg, bp, bb, a.counts,
+                                               a.offsets, a.gate_sum, a.prob_sum, a.lb_loss);
+  BTX_LAUNCH_CHECK();
+  route_scatter_kernel<<<ceil_div(nblk, kWavesPerBlock), kWavesPerBlock * kWave, 0, s>>>(
+      nblk, a.T, a.E, a.k, a.topk_idx, bb, a.offsets, a.perm, a.inv_pos);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+}  // namespace btx

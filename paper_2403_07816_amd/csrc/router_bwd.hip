@@ -1,0 +1,225 @@
+// Backward of the router and the last step of dX (chain rule on the routing function of
+// Sec. 3.2 / 3.3 with the expert selection held fixed, plus the gradient of the
+// load-balancing loss of Sec. 3.3).  All reductions run in a fixed order; no atomics.
+//
+//   router_ds       one wavefront per token, lane e = expert e: dg (summed partials of
+//                   <dY, expert output>), gate Jacobian, load-balancing term -> ds[T,E]
+//   dwr_partial     dW_router = x^T ds as per-token-chunk partial sums
+//   dwr_reduce      fixed-order sum of the partials (and of db_router)
+//   dx_finish       dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T
+#include "common.h"
+
+namespace btx {
+namespace {
+
+constexpr int kTokChunk = 64;   // tokens per dW_router partial
+constexpr int kColsPerThread = 8;
+constexpr int kEC = 8;          // experts per dW_router pass
+
+__global__ __launch_bounds__(256) void router_ds_kernel(
+    int T, int E, int k, int mode, int lb_mode, float lb_alpha, float lam, unsigned flags,
+    const int32_t* __restrict__ topk_idx, const float* __restrict__ gates, const float* __restrict__ probs,
+    const int32_t* __restrict__ inv_pos, const float* __restrict__ gate_sum, const float* __restrict__ prob_sum,
+    const int32_t* __restrict__ counts, const float* __restrict__ dg_part, int n_part, float* __restrict__ ds) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int t = blockIdx.x * 4 + threadIdx.x / kWave;
+  if (t >= T) return;
+  const bool live = lane < E;
+  const float lbc = lb_alpha * (float)E / (float)T;
+  const float pbar = live ? prob_sum[lane] / (float)T : 0.f;
+  // lane j < k: slot j of this token
+  int my_e = -1;
+  float g = 0.f, dg = 0.f;
+  if (lane < k) {
+    my_e = topk_idx[(size_t)t * k + lane];
+    g = gates[(size_t)t * k + lane];
+    const float* part = dg_part + (size_t)inv_pos[(size_t)t * k + lane] * n_part;
+    for (int p = 0; p < n_part; ++p) dg += part[p];
+  }
+  if (flags & BTX_FLAG_LB_GRAD_THROUGH_U) {
+    const float pb = __shfl(pbar, my_e < 0 ? 0 : my_e, kWave);
+    if (lane < k) dg += lam * lbc * pb;
+  }
+  const float p = live ? probs[(size_t)t * E + lane] : 0.f;
+  float dsv = 0.f;
+  if (mode == BTX_ROUTE_TOPK_RENORM) {
+    const float inner = wave_sum(g * dg);  // lanes >= k contribute 0
+    const float mine = g * (dg - inner);
+    for (int j = 0; j < k; ++j) {
+      const int e = __shfl(my_e, j, kWave);
+      const float v = __shfl(mine, j, kWave);
+      if (lane == e) dsv = v;
+    }
+  } else {
+    const int e = __shfl(my_e, 0, kWave);
+    const float dg0 = __shfl(dg, 0, kWave);
+    const float pe = __shfl(p, e, kWave);
+    dsv = dg0 * pe * ((lane == e ? 1.f : 0.f) - p);
+  }
+  if (lam != 0.f) {
+    const float u = !live ? 0.f
+                    : lb_mode == BTX_LB_TOKEN_FRAC ? (float)counts[lane] / ((float)T * (float)k)
+                                                   : gate_sum[lane] / (float)T;
+    const float up = wave_sum(u * p);
+    dsv += lam * lbc * p * (u - up);
+  }
+  if (live) ds[(size_t)t * E + lane] = dsv;
+}
+
+template <typename XT> struct Ld8;
+template <> struct Ld8<bf16_t> {
+  static __device__ __forceinline__ void ld(const bf16_t* p, float* v) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, const float* v) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+    *reinterpret_cast<u32x4*>(p) = w;
+  }
+};
+template <> struct Ld8<float> {
+  static __device__ __forceinline__ void ld(const float* p, float* v) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+  static __device__ __forceinline__ void st(float* p, const float* v) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+  }
+};
+
+// grid: (token chunks, column blocks of 256*8, expert passes of kEC)
+template <typename XT>
+__global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__ x, const float* __restrict__ ds, int T,
+                                                          int d, int E, float* __restrict__ part,
+                                                          float* __restrict__ db_part) {
+  __shared__ float s_ds[kTokChunk][kEC];
+  const int t0 = blockIdx.x * kTokChunk, e0 = blockIdx.z * kEC;
+  const int nt = min(kTokChunk, T - t0);
+  for (int i = threadIdx.x; i < kTokChunk * kEC; i += 256) {
+    const int q = i / kEC, j = i % kEC;
+    s_ds[q][j] = (q < nt && e0 + j < E) ? ds[(size_t)(t0 + q) * E + e0 + j] : 0.f;
+  }
+  __syncthreads();
+  const int c0 = (blockIdx.y * 256 + threadIdx.x) * kColsPerThread;
+  if (c0 < d) {
+    float acc[kColsPerThread][kEC] = {};
+    for (int q = 0; q < nt; ++q) {
+      float xv[8];
+      Ld8<XT>::ld(x + (size_t)(t0 + q) * d + c0, xv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < kEC; ++j) acc[i][j] = fmaf(xv[i], s_ds[q][j], acc[i][j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < kEC; ++j)
+        if (e0 + j < E) part[((size_t)blockIdx.x * d + c0 + i) * E + e0 + j] = acc[i][j];
+  }
+  if (blockIdx.y == 0 && threadIdx.x < kEC && e0 + threadIdx.x < E) {
+    float a = 0.f;
+    for (int q = 0; q < nt; ++q) a += s_ds[q][threadIdx.x];
+    db_part[(size_t)blockIdx.x * E + e0 + threadIdx.x] = a;
+  }
+}
+
+__global__ __launch_bounds__(256) void dwr_reduce_kernel(const float* __restrict__ part, const float* __restrict__ db_part,
+                                                         int nchunk, int dE, int E, float* __restrict__ dWr,
+                                                         float* __restrict__ db) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < dE) {
+    float a = 0.f;
+    for (int c = 0; c < nchunk; ++c) a += part[(size_t)c * dE + i];
+    dWr[i] = a;
+  }
+  if (db && blockIdx.x == 0 && threadIdx.x < E) {
+    float a = 0.f;
+    for (int c = 0; c < nchunk; ++c) a += db_part[(size_t)c * E + threadIdx.x];
+    db[threadIdx.x] = a;
+  }
+}
+
+// One wavefront per token row.
+template <typename XT>
+__global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ dxs, const int32_t* __restrict__ inv_pos,
+                                                        const float* __restrict__ ds, const float* __restrict__ Wr,
+                                                        int T, int d, int E, int k, XT* __restrict__ dX) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int t = blockIdx.x * 4 + threadIdx.x / kWave;
+  if (t >= T) return;
+  const float my_ds = lane < E ? ds[(size_t)t * E + lane] : 0.f;
+  // The trip count is uniform so that every lane stays active for the cross-lane reads of ds.
+  for (int base = 0; base < d; base += kWave * 8) {
+    const int c0 = base + lane * 8;
+    const bool in_row = c0 < d;
+    float acc[8] = {};
+    if (in_row) {
+      for (int j = 0; j < k; ++j) {
+        const int r = inv_pos[(size_t)t * k + j];
+        float v[8];
+        Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+      }
+    }
+    for (int e = 0; e < E; ++e) {
+      const float w = __shfl(my_ds, e, kWave);
+      if (w != 0.f && in_row) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, Wr[(size_t)(c0 + i) * E + e], acc[i]);
+      }
+    }
+    if (in_row) Ld8<XT>::st(dX + (size_t)t * d + c0, acc);
+  }
+}
+
+}  // namespace
+
+static int n_chunks(int T) { return ceil_div(T, kTokChunk); }
+
+size_t router_bwd_workspace_bytes(int T, int d, int E) {
+  const size_t ds = align_up((size_t)T * E * sizeof(float), 256);
+  const size_t part = align_up((size_t)n_chunks(T) * d * E * sizeof(float), 256);
+  const size_t dbp = align_up((size_t)n_chunks(T) * E * sizeof(float), 256);
+  return ds + part + dbp;
+}
+
+int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
+  char* w = static_cast<char*>(a.workspace);
+  float* ds = reinterpret_cast<float*>(w);
+  w += align_up((size_t)a.T * a.E * sizeof(float), 256);
+  float* part = reinterpret_cast<float*>(w);
+  w += align_up((size_t)n_chunks(a.T) * a.d * a.E * sizeof(float), 256);
+  float* dbp = reinterpret_cast<float*>(w);
+
+  router_ds_kernel<<<ceil_div(a.T, 4), 256, 0, s>>>(a.T, a.E, a.k, a.route_mode, a.lb_mode, a.lb_alpha, a.lb_grad_scale,
+                                                   a.flags, a.topk_idx, a.gates, a.probs, a.inv_pos, a.gate_sum,
+                                                   a.prob_sum, a.counts, a.dg_part, a.n_part, ds);
+  BTX_LAUNCH_CHECK();
+  dim3 grid(n_chunks(a.T), ceil_div(a.d, 256 * kColsPerThread), ceil_div(a.E, kEC));
+  if (a.dtype == BTX_BF16)
+    dwr_partial_kernel<bf16_t><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(a.x), ds, a.T, a.d, a.E, part, dbp);
+  else
+    dwr_partial_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(a.x), ds, a.T, a.d, a.E, part, dbp);
+  BTX_LAUNCH_CHECK();
+  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 256), 256, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E, a.E,
+                                                                      a.dW_router, a.db_router);
+  BTX_LAUNCH_CHECK();
+  if (a.dtype == BTX_BF16)
+    dx_finish_kernel<bf16_t><<<ceil_div(a.T, 4), 256, 0, s>>>(static_cast<const bf16_t*>(a.dxs), a.inv_pos, ds,
+                                                             a.W_router, a.T, a.d, a.E, a.k,
+                                                             static_cast<bf16_t*>(a.dX));
+  else
+    dx_finish_kernel<float><<<ceil_div(a.T, 4), 256, 0, s>>>(static_cast<const float*>(a.dxs), a.inv_pos, ds,
+                                                            a.W_router, a.T, a.d, a.E, a.k, static_cast<float*>(a.dX));
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+}  // namespace btx

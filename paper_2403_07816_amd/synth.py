@@ -49,13 +49,15 @@ def make_layer(T: int, d: int, f: int, E: int, *, dtype: torch.dtype = torch.flo
                seed: int = BASE_SEED, device: str = "cpu", unit_rms: bool = False,
                router_E: Optional[int] = None, router_bias: Optional[Sequence[float]] = None,
                with_dY: bool = False, with_U: bool = False,
-               identical_experts: bool = False) -> Dict[str, Optional[torch.Tensor]]:
+               identical_experts: bool = False, expert_spread: float = 0.1) -> Dict[str, Optional[torch.Tensor]]:
     """Draw one layer's inputs and parameters.
 
     E is the number of seed-shaped expert FFNs (each [d,f]); router_E is the
     number of router columns (differs from E only when the caller will split
     every FFN into chunks afterwards).  identical_experts=True leaves out the
-    per-expert perturbation (the sparse-upcycling initialisation).
+    per-expert perturbation (the sparse-upcycling initialisation); expert_spread
+    is the perturbation's std in units of the seed's (0.1 in the workload recipe;
+    1.0 makes the experts nearly unrelated).
     """
     router_E = E if router_E is None else router_E
     x = _randn((T, d), 1.0, seed, _STREAM["x"], device)
@@ -70,7 +72,7 @@ def make_layer(T: int, d: int, f: int, E: int, *, dtype: torch.dtype = torch.flo
             if identical_experts:
                 stacked[e] = base.to(dtype)
             else:
-                pert = _randn(shape, 0.1 / math.sqrt(fan_in), seed, _STREAM["pert_" + name] + e, device)
+                pert = _randn(shape, expert_spread / math.sqrt(fan_in), seed, _STREAM["pert_" + name] + e, device)
                 stacked[e] = (base + pert).to(dtype)
                 del pert
         out["W" + name[1]] = stacked

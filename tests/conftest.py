@@ -25,5 +25,8 @@ def rel_err(a, b):
 
 
 def assert_close(a, b, tol, what=""):
+    """Both relative measures must stay within tol: Frobenius norm of the
+    difference over that of the reference, and largest absolute difference
+    over the largest reference magnitude."""
     fro, mx = rel_err(a, b)
     assert fro <= tol and mx <= tol, f"{what}: fro_rel={fro:.3e} max_rel={mx:.3e} tol={tol:.1e}"

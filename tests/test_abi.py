@@ -1,0 +1,108 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+function the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2403_07816_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2403_07816_amd.build import build
+        build(verbose=False)
+    return B.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "btx_moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(btx_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = declared_functions()
+    for required in ("btx_moe_route", "btx_moe_ff_forward", "btx_moe_ff_backward", "btx_merge_average"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in btx_moe.h but not exported"
+    assert lib.btx_version() >= 1
+    assert lib.btx_status_string(0) == b"ok"
+
+
+def test_binding_covers_every_declared_symbol():
+    assert sorted(B._SIGNATURES) == declared_functions()
+
+
+def test_route_rejects_bad_arguments(lib):
+    p = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    null = None
+
+    def route(T=8, d=64, E=4, k=2, mode=0, lb=0, U=null, x=p, ws_bytes=1 << 20, dtype=0):
+        return lib.btx_moe_route(x, dtype, p, null, U, T, d, E, k, mode, lb, 0.0, p, p, p, p, p, p, p, p, p, p, p,
+                                 ws_bytes, null)
+
+    assert route(k=5) == 1                 # k > E
+    assert route(k=0) == 1
+    assert route(E=65, k=1) == 1           # more experts than a wavefront has lanes
+    assert route(d=60) == 1                # d not a multiple of 8
+    assert route(mode=3) == 1
+    assert route(mode=1, k=2) == 1         # Switch needs k = 1
+    assert route(mode=2, k=1) == 1         # sampling needs U
+    assert route(mode=0, U=p) == 1         # U only with sampling
+    assert route(lb=2) == 1
+    assert route(dtype=7) == 1
+    assert route(x=null) == 1
+    assert route(ws_bytes=16) == 3         # workspace too small
+    assert route(T=0) == 0                 # empty batch: nothing to do
+    assert route(T=-1) == 1
+
+
+def test_forward_backward_and_merge_reject_bad_arguments(lib):
+    p = ctypes.c_void_p(256)
+    null = None
+
+    def fwd(T=8, d=64, f=64, E=4, k=2, s13=64 * 64, s2=64 * 64, h1=p, h3=p, ws=1 << 30, out=p):
+        return lib.btx_moe_ff_forward(p, p, p, p, 0, s13, s2, T, d, f, E, k, p, p, p, p, out, h1, h3, p, ws, null)
+
+    assert fwd(f=12) == 1
+    assert fwd(s13=10) == 1                # expert stride smaller than one expert
+    assert fwd(h3=null) == 1               # h1/h3 come as a pair
+    assert fwd(out=null) == 1
+    assert fwd(ws=0) == 3
+    assert fwd(T=0) == 0
+
+    def bwd(T=8, k=2, mode=0, lb=0, flags=0, dW=(p, p, p), dwt=0, dt=0, ws=1 << 30):
+        return lib.btx_moe_ff_backward(p, p, p, p, p, p, dt, 64 * 64, 64 * 64, T, 64, 64, 4, k, mode, lb, 0.0, 0.0,
+                                       flags, p, p, p, p, p, p, p, p, p, p, p, p, p, null, dW[0], dW[1], dW[2], dwt,
+                                       p, ws, null)
+
+    assert bwd(dW=(p, null, p)) == 1       # weight gradients: all three or none
+    assert bwd(flags=1, lb=0) == 1         # gradient through u only in gate-mean mode
+    assert bwd(flags=8) == 1
+    assert bwd(dt=0, dwt=1) == 1           # fp32 layer cannot return bf16 weight gradients
+    assert bwd(mode=1, k=2) == 1
+    assert bwd(ws=0) == 3
+    assert bwd(T=0) == 0
+
+    arr = (ctypes.c_void_p * 2)(256, 512)
+    assert lib.btx_merge_average(arr, 0, p, 16, 0, null) == 1
+    assert lib.btx_merge_average(arr, 17, p, 16, 0, null) == 1
+    assert lib.btx_merge_average(arr, 2, ctypes.c_void_p(257), 16, 0, null) == 1   # misaligned
+    assert lib.btx_merge_average(arr, 2, p, 0, 0, null) == 0
+    assert lib.btx_merge_average(arr, 2, p, -1, 0, null) == 1
+
+
+def test_missing_library_raises(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libbtx_moe.so")
+    with pytest.raises(RuntimeError):
+        B.load_library()
