@@ -10,32 +10,38 @@ size_t ff_scratch_bytes(int dtype, int R, int f) {
   return align_up((size_t)R * f * sizeof(float), 256);  // dys W2^T before its elementwise step
 }
 
-int bwd_act_partials(int /*dtype*/, int /*f*/) { return 1; }
+// The MFMA kernels need d and f to be multiples of 32; other bf16 shapes take the plain path.
+static bool mfma_shape(int d, int f) { return d % 32 == 0 && f % 32 == 0 && d >= 64 && f >= 64; }
+
+int bwd_act_partials(int dtype, int f) { return dtype == BTX_BF16 ? mfma_bwd_act_partials(f) : 1; }
 
 int launch_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* /*scratch*/, hipStream_t s) {
-  if (dtype == BTX_BF16) return mfma_up_swiglu(xs, W1, W3, offsets, sh, h1, h3, act, s);
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_up_swiglu(xs, W1, W3, offsets, sh, h1, h3, act, s);
   return generic_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, act, s);
 }
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
                 hipStream_t s) {
-  if (dtype == BTX_BF16) return mfma_down(act, W2, offsets, sh, y, s);
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_down(act, W2, offsets, sh, y, s);
   return generic_down(dtype, act, W2, offsets, sh, y, s);
 }
 int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                    float* dg_part, void* scratch, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) {
+    return mfma_bwd_act(dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, s);
+  }
   return generic_bwd_act(dtype, dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, scratch, s);
 }
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
                   const FfShapes& sh, void* dxs, hipStream_t s) {
-  if (dtype == BTX_BF16) return mfma_bwd_dx(dh1, dh3, W1, W3, offsets, sh, dxs, s);
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dx(dh1, dh3, W1, W3, offsets, sh, dxs, s);
   return generic_bwd_dx(dtype, dh1, dh3, W1, W3, offsets, sh, dxs, s);
 }
 int launch_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
                   const void* dys, const int32_t* offsets, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
                   hipStream_t s) {
-  if (dtype == BTX_BF16) return mfma_bwd_dw(dW_dtype, xs, dh1, dh3, ga, dys, offsets, sh, dW1, dW3, dW2, s);
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dw(dW_dtype, xs, dh1, dh3, ga, dys, offsets, sh, dW1, dW3, dW2, s);
   return generic_bwd_dw(dtype, dW_dtype, xs, dh1, dh3, ga, dys, offsets, sh, dW1, dW3, dW2, s);
 }
 

@@ -1,12 +1,507 @@
-// bf16 expert GEMMs.  (Temporary: routed through the plain FMA kernels.)
+// bf16 MFMA grouped GEMMs of the expert FFNs (the SwiGLU feed-forward FF_i of the layer
+// equation in Sec. 3.2, forward and backward), written for gfx950.
+//
+// One kernel template covers the six products of the layer:
+//   UP      h1 = xs W1_e, h3 = xs W3_e, act = silu(h1)*h3          (two B panels share one A tile)
+//   DOWN    y = act W2_e
+//   BWD_ACT D = dys W2_e^T with the SwiGLU backward fused into the epilogue
+//   BWD_DX  dxs = dh1 W1_e^T + dh3 W3_e^T                           (two K passes, one accumulator)
+//   DW13    dW1_e = xs_e^T dh1_e, dW3_e = xs_e^T dh3_e              (K = the expert's ragged row count)
+//   DW2     dW2_e = ga_e^T dys_e
+//
+// Structure of a workgroup (WM x WN wavefronts, BM x BN x BK tile):
+//   * global -> LDS copies are direct (global_load_lds, 16 bytes per lane, no VGPR staging),
+//     NSTAGE tiles in flight, one barrier per K step;
+//   * an operand whose K index is contiguous in memory is stored [row][BK] with a 16-byte
+//     chunk XOR swizzle and read with ds_read_b128; an operand whose K index is strided
+//     (weights in the forward pass, everything in the dW products) is stored as it lies in
+//     memory, [BK][cols], and read with the transposing ds_read_b64_tr_b16, so no operand is
+//     ever transposed in registers or in HBM.  The swizzles are applied by choosing which
+//     global chunk each lane fetches, since a direct copy fixes the LDS position per lane;
+//   * v_mfma_f32_32x32x16_bf16 with the roles of the operands swapped (the N-side fragment is
+//     passed first), so that each lane ends up with 4 consecutive output columns of one row
+//     and stores 8 bytes at a time;
+//   * grouped rows: tiles are enumerated per expert on the device (no host sync); a tile past
+//     the last one exits.  Rows beyond a group's end are loaded from a clamped address and
+//     never stored.  In the dW products the K tail is zeroed in registers.
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
+
 namespace btx {
-int mfma_bwd_act_partials(int) { return 1; }
-int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* h1,
-                   void* h3, void* act, hipStream_t s) { return generic_up_swiglu(BTX_BF16, xs, W1, W3, off, sh, h1, h3, act, s); }
-int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s) { return generic_down(BTX_BF16, act, W2, off, sh, y, s); }
-int mfma_bwd_act(const void*, const void*, const void*, const void*, const float*, const int32_t*, const int32_t*, const FfShapes&, void*, void*, void*, float*, hipStream_t) { return BTX_ERR_UNSUPPORTED; }
-int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* dxs, hipStream_t s) { return generic_bwd_dx(BTX_BF16, dh1, dh3, W1, W3, off, sh, dxs, s); }
-int mfma_bwd_dw(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2, hipStream_t s) { return generic_bwd_dw(BTX_BF16, dW_dtype, xs, dh1, dh3, ga, dys, off, sh, dW1, dW3, dW2, s); }
+namespace {
+
+enum Mode { UP = 0, DOWN = 1, BWD_ACT = 2, BWD_DX = 3, DW13 = 4, DW2 = 5 };
+
+struct MArgs {
+  const bf16_t* A0; const bf16_t* A1;   // A1: second K pass (BWD_DX)
+  const bf16_t* B0; const bf16_t* B1;   // B1: second panel (UP, DW13) or second K pass (BWD_DX)
+  void* C0; void* C1; void* C2;         // UP: h1,h3,act; BWD_ACT: dh1,dh3,ga; DW13: dW1,dW3; else C0
+  const bf16_t* H1; const bf16_t* H3;   // BWD_ACT inputs
+  const float* gates; const int32_t* perm; float* dg_part; int n_part;
+  const int32_t* offsets; int E;
+  int M, N, K;                          // grouped-M: M unused; grouped-K: K unused
+  int lda, ldb, ldc;                    // leading dimensions in elements
+  int64_t strideB_e, strideC_e;         // per-expert strides in elements
+  int R;                                // total grouped rows
+  int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
+  int c_is_f32;
+};
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+  // gfx9 encoding: vmcnt = bits [3:0] and [15:14]; expcnt [6:4] and lgkmcnt [11:8] left at max
+  switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    case 16: __builtin_amdgcn_s_waitcnt(0x4F70); break;
+    case 24: __builtin_amdgcn_s_waitcnt(0x4F78); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
 }
+
+// Direct global -> LDS copy of 16 bytes per lane: lane l's data lands at lds_base + 16*l.
+// Written as inline assembly so that the compiler does not serialise later LDS reads of
+// *other* stages behind it (it cannot tell the stages apart and would wait for vmcnt(0));
+// completion is awaited explicitly with wait_vmcnt() before the barrier that publishes a tile.
+// `base` and `lds_base` are wave-uniform by construction; readfirstlane states that to the
+// compiler where its divergence analysis cannot see it.
+__device__ __forceinline__ void copy16_to_lds(const void* base, uint32_t byte_off, uint32_t lds_base) {
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  // readfirstlane returns int: go through uint32_t so that the halves are not sign-extended
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+  const uint64_t sp = (uint64_t)lo | ((uint64_t)hi << 32);
+  const uint32_t sl = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(sl), "v"(byte_off), "s"(sp)
+               : "memory");
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+struct Gemm {
+  static constexpr bool A_KC = (MODE != DW13 && MODE != DW2);   // A's K index contiguous in memory
+  static constexpr bool B_KC = (MODE == BWD_ACT || MODE == BWD_DX);
+  static constexpr bool DUAL = (MODE == UP || MODE == DW13);
+  static constexpr bool GROUP_K = (MODE == DW13 || MODE == DW2);
+  static constexpr int NW = WM * WN, NT = NW * kWave;
+  static constexpr int TM = BM / WM / 32;                      // 32-row fragments per wavefront
+  static constexpr int TN = BN / WN / 32;
+  static constexpr int TNH = DUAL ? TN / 2 : TN;
+  static constexpr int BNH = DUAL ? BN / 2 : BN;               // output columns per B panel
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = STAGE_BYTES * NSTAGE;
+  static constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // per wavefront per tile
+  static constexpr int KSTEPS = BK / 16;
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split into 1 KB wave copies");
+  static_assert(TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "bad wave tiling");
+  static_assert(BK == 32 || BK == 64, "BK");
+
+  // ---- LDS addressing ----------------------------------------------------
+  // K-contiguous tile: [rows][BK], 16-byte chunks XOR-swizzled by row
+  static __device__ __forceinline__ int kc_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  // strided-K tile: [BK][COLS], 16-byte chunk index XORed with (k & 3) << 2
+
+  // byte offset inside a wave's copy `seg` (1 KB each) -> global element offset, for both layouts
+  template <bool KC, int ROWS_OR_COLS>
+  static __device__ __forceinline__ void copy_coords(int seg, int lane, int& major, int& minor_elem) {
+    const int o = seg * 1024 + lane * 16;
+    if (KC) {
+      const int row = o / (BK * 2);
+      const int phys = (o % (BK * 2)) / 16;
+      major = row;                              // row of the tile (M or N index)
+      minor_elem = (phys ^ kc_swz(row)) * 8;    // k offset inside the tile
+    } else {
+      constexpr int PITCH = ROWS_OR_COLS * 2;
+      const int k = o / PITCH;
+      const int phys = (o % PITCH) / 16;
+      major = k;                                // k row of the tile
+      minor_elem = (phys ^ ((k & 3) << 2)) * 8; // column offset inside the tile
+    }
+  }
+
+  static __device__ __forceinline__ bf16x8 read_kc(const char* tile, int row, int ks, int lane) {
+    const int r = row + (lane & 31);
+    const int chunk = 2 * ks + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(tile + r * (BK * 2) + ((chunk ^ kc_swz(r)) << 4));
+  }
+  template <int COLS>
+  static __device__ __forceinline__ bf16x8 read_tr(const char* tile, int col, int ks, int lane) {
+    const int g = lane >> 4, r = lane & 15;
+    const int k = 16 * ks + 8 * (g >> 1) + (r >> 2);
+    const int c = col + 16 * (g & 1) + 4 * (r & 3);
+    const int off = k * (COLS * 2) + ((((c >> 3) ^ ((r >> 2) << 2)) << 4) | ((c & 7) << 1));
+    typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(tile + off));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(tile + off + 4 * COLS * 2));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+
+  static __device__ void run(const MArgs& g, char* smem) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- which tile ------------------------------------------------------
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+    // tile ids so that tiles sharing operand panels meet in one L2, then walk the range in
+    // groups of kGroupM row tiles x all column tiles.
+    const int total = g.tiles_m * g.tiles_n * (GROUP_K ? g.E : 1);
+    int id = blockIdx.x;
+    {
+      const int per = total / 8, rem = total % 8, x = id % 8, q = id / 8;
+      // XCD x owns per (+1 if x < rem) ids starting at x*per + min(x, rem)
+      id = x * per + (x < rem ? x : rem) + q;
+    }
+    int e = 0;
+    if (GROUP_K) {
+      const int per_e = g.tiles_m * g.tiles_n;
+      e = id / per_e;
+      id -= e * per_e;
+    }
+    constexpr int kGroupM = 4;
+    const int gsz = kGroupM * g.tiles_n;
+    const int grp = id / gsz, in = id % gsz;
+    const int m_first = grp * kGroupM;
+    const int m_cnt = min(kGroupM, g.tiles_m - m_first);
+    const int tile_m = m_first + in % m_cnt, tile_n = in / m_cnt;
+
+    int row0, row_end, k_begin, k_end;
+    if (GROUP_K) {
+      row0 = tile_m * BM;
+      row_end = g.M;
+      k_begin = g.offsets[e];
+      k_end = g.offsets[e + 1];
+    } else {
+      if (!find_row_tile(g.offsets, g.E, BM, tile_m, e, row0, row_end)) return;
+      k_begin = 0;
+      k_end = g.K;
+    }
+    const int col0 = tile_n * BNH;
+
+    const bf16_t* Bp0 = g.B0;
+    const bf16_t* Bp1 = g.B1;
+    if (!GROUP_K) { Bp0 += e * g.strideB_e; if (Bp1) Bp1 += e * g.strideB_e; }
+
+    // ---- per-lane byte offsets of the direct copies, relative to a per-tile uniform base --
+    // KC operand:      base = P + row0*ld + k0,  offset = (clamp(row) - row0)*ld + k_in_tile
+    // strided operand: base = P + k0*ld,         offset = k_in_tile*ld + clamp(col)
+    uint32_t a_off[A_LOADS], b_off[B_LOADS];
+    int a_k[A_LOADS], b_k[B_LOADS], a_c[A_LOADS], b_c[B_LOADS];   // strided layouts: k row / column
+    bool b_second[B_LOADS];
+#pragma unroll
+    for (int q = 0; q < A_LOADS; ++q) {
+      int major, minor;
+      copy_coords<A_KC, BM>(wave * A_LOADS + q, lane, major, minor);
+      if (A_KC) {
+        a_off[q] = (uint32_t)((min(row0 + major, row_end - 1) - row0) * g.lda + minor) * 2u;
+        a_k[q] = a_c[q] = 0;
+      } else {
+        a_k[q] = major;
+        a_c[q] = min(row0 + minor, row_end - 8);
+        a_off[q] = (uint32_t)(major * g.lda + a_c[q]) * 2u;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < B_LOADS; ++q) {
+      int major, minor;
+      // DUAL: the B tile is two panels [BK][BNH] back to back, so one wave copy (1 KB) never
+      // straddles W1 and W3 and its base pointer stays uniform
+      constexpr int SEGS_PER_PANEL = B_BYTES / 1024 / (DUAL ? 2 : 1);
+      const int seg = wave * B_LOADS + q;
+      copy_coords<B_KC, BNH>(seg % SEGS_PER_PANEL, lane, major, minor);
+      if (B_KC) {
+        // tile rows are output columns; BWD_DX / BWD_ACT have a single panel
+        b_off[q] = (uint32_t)((min(col0 + major, g.N - 1) - col0) * g.ldb + minor) * 2u;
+        b_k[q] = b_c[q] = 0;
+        b_second[q] = false;
+      } else {
+        b_k[q] = major;
+        b_c[q] = min(col0 + minor, g.N - 8);
+        b_off[q] = (uint32_t)(major * g.ldb + b_c[q]) * 2u;
+        b_second[q] = DUAL && seg >= SEGS_PER_PANEL;     // uniform across the wavefront
+      }
+    }
+
+    const int k_len = k_end - k_begin;
+    const int nk1 = (k_len + BK - 1) / BK;
+    const int nk = MODE == BWD_DX ? 2 * nk1 : nk1;
+    const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
+
+    auto issue = [&](int kt) {
+      const uint32_t stage = smem_base + (kt % NSTAGE) * STAGE_BYTES;
+      const bool pass2 = MODE == BWD_DX && kt >= nk1;
+      const int k0 = k_begin + (pass2 ? kt - nk1 : kt) * BK;
+      const bf16_t* Ab = pass2 ? g.A1 : g.A0;
+      Ab += A_KC ? (size_t)row0 * g.lda + k0 : (size_t)k0 * g.lda;
+#pragma unroll
+      for (int q = 0; q < A_LOADS; ++q) {
+        uint32_t off = a_off[q];
+        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
+        if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
+        copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
+      }
+      const bf16_t* B0b = Bp0 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
+      const bf16_t* B1b = Bp1 ? Bp1 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb) : nullptr;
+#pragma unroll
+      for (int q = 0; q < B_LOADS; ++q) {
+        uint32_t off = b_off[q];
+        if (GROUP_K) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
+        const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[q]);
+        copy16_to_lds(second ? B1b : B0b, off, stage + A_BYTES + (wave * B_LOADS + q) * 1024);
+      }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    constexpr int PER_TILE = A_LOADS + B_LOADS;
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nk) issue(s);
+
+    for (int kt = 0; kt < nk; ++kt) {
+      // tile kt must have landed; up to NSTAGE-2 younger tiles may still be in flight
+      if (kt + NSTAGE - 2 < nk) wait_vmcnt((NSTAGE - 2) * PER_TILE);
+      else wait_vmcnt(0);
+      __syncthreads();
+      if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+
+      const char* stage = smem + (kt % NSTAGE) * STAGE_BYTES;
+      const char* At = stage;
+      const char* Bt = stage + A_BYTES;
+      const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int r = wm * (TM * 32) + i * 32;
+          af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
+        }
+        if (k_tail) {
+          // grouped-K: rows past the expert's last one belong to the next expert; zero A there
+          const int kb = kt * BK + ks * 16 + 8 * (lane >> 5);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+              if (kb + x >= k_len) af[i][x] = (__bf16)0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int c = wn * (TNH * 32) + (j % TNH) * 32;
+          bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+      }
+    }
+
+    // ---- epilogue ----------------------------------------------------------
+    // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
+    //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
+    const int lane_m = lane & 31, lane_h = lane >> 5;
+    float dg_acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) dg_acc[i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int m = row0 + wm * (TM * 32) + i * 32 + lane_m;
+      const bool m_ok = m < row_end;
+      float gate = 0.f;
+      if (MODE == BWD_ACT && m_ok) gate = g.gates[g.perm[m]];
+#pragma unroll
+      for (int j = 0; j < TNH; ++j) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h;
+          if (!m_ok || n >= g.N) continue;
+          const size_t idx = (size_t)m * g.ldc + n;
+          if (MODE == UP) {
+            float h1[4], h3[4], a[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              h1[x] = acc[i][j][4 * q + x];
+              h3[x] = acc[i][j + TNH][4 * q + x];
+              a[x] = silu_f(h1[x]) * h3[x];
+            }
+            if (g.C0) {
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
+                  u32x2{pack_bf16x2(h1[0], h1[1]), pack_bf16x2(h1[2], h1[3])};
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
+                  u32x2{pack_bf16x2(h3[0], h3[1]), pack_bf16x2(h3[2], h3[3])};
+            }
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
+                u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
+          } else if (MODE == BWD_ACT) {
+            const u32x2 w1 = *reinterpret_cast<const u32x2*>(g.H1 + idx);
+            const u32x2 w3 = *reinterpret_cast<const u32x2*>(g.H3 + idx);
+            const float z[4] = {bf16lo(w1[0]), bf16hi(w1[0]), bf16lo(w1[1]), bf16hi(w1[1])};
+            const float v3[4] = {bf16lo(w3[0]), bf16hi(w3[0]), bf16lo(w3[1]), bf16hi(w3[1])};
+            float o1[4], o3[4], oa[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              const float dd = acc[i][j][4 * q + x];
+              const float sg = sigmoid_f(z[x]), sl = z[x] * sg;
+              const float a = sl * v3[x];
+              dg_acc[i] = fmaf(dd, a, dg_acc[i]);
+              const float da = gate * dd;
+              o1[x] = da * v3[x] * (sg * (1.f + z[x] * (1.f - sg)));
+              o3[x] = da * sl;
+              oa[x] = gate * a;
+            }
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
+                u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
+                u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
+                u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
+          } else {
+            // plain stores: DOWN, BWD_DX (bf16); DW13 / DW2 (bf16 or fp32, per-expert base)
+            const size_t cidx = idx + (GROUP_K ? (size_t)e * g.strideC_e : 0);
+#pragma unroll
+            for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
+              const f32x16& t = acc[i][j + p * TNH];
+              void* C = p ? g.C1 : g.C0;
+              if (GROUP_K && g.c_is_f32) {
+                *reinterpret_cast<f32x4*>(static_cast<float*>(C) + cidx) =
+                    f32x4{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
+              } else {
+                *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(C) + cidx) =
+                    u32x2{pack_bf16x2(t[4 * q], t[4 * q + 1]), pack_bf16x2(t[4 * q + 2], t[4 * q + 3])};
+              }
+            }
+          }
+        }
+      }
+    }
+    if (MODE == BWD_ACT) {
+      // dg partial of this column tile: lanes l and l^32 hold the same row; then the WN
+      // wavefronts of a row band are summed in fixed order through LDS.
+      __syncthreads();  // all waves are done with the operand tiles
+      float* red = reinterpret_cast<float*>(smem);   // [WN][BM]
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const float s = dg_acc[i] + __shfl_xor(dg_acc[i], 32, kWave);
+        if (lane_h == 0) red[wn * BM + wm * (TM * 32) + i * 32 + lane_m] = s;
+      }
+      __syncthreads();
+      for (int r = threadIdx.x; r < BM; r += NT) {
+        const int m = row0 + r;
+        if (m < row_end) {
+          float s = 0.f;
+#pragma unroll
+          for (int w = 0; w < WN; ++w) s += red[w * BM + r];
+          g.dg_part[(size_t)m * g.n_part + tile_n] = s;
+        }
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+__global__ __launch_bounds__(WM* WN* kWave) void mfma_gemm_kernel(MArgs g) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  Gemm<BM, BN, BK, WM, WN, NSTAGE, MODE>::run(g, smem);
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+int launch(MArgs g, hipStream_t s) {
+  using G = Gemm<BM, BN, BK, WM, WN, NSTAGE, MODE>;
+  constexpr int BNH = G::DUAL ? BN / 2 : BN;
+  g.tiles_n = ceil_div(g.N, BNH);
+  g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
+  const int total = g.tiles_m * g.tiles_n * (G::GROUP_K ? g.E : 1);
+  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSTAGE, MODE>;
+  static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            G::LDS_BYTES) != hipSuccess)
+      return BTX_ERR_HIP;
+    attr_set = true;
+  }
+  kern<<<total, G::NT, G::LDS_BYTES, s>>>(g);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+// The direct-copy loaders need whole 16-byte chunks inside every row and K multiples of BK
+// where K is a matrix dimension.
+bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh.d >= 64 && sh.f >= 64; }
+
+}  // namespace
+
+constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
+int mfma_bwd_act_partials(int f) { return ceil_div(f, kActBN); }
+
+int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* h1,
+                   void* h3, void* act, hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
+  MArgs g{};
+  g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
+  g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
+  g.strideB_e = sh.s13; g.R = sh.R;
+  return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, UP>(g, s);
+}
+
+int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
+  MArgs g{};
+  g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y;
+  g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.d; g.ldc = sh.d;
+  g.strideB_e = sh.s2; g.R = sh.R;
+  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, DOWN>(g, s);
+}
+
+int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+                 const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* ga,
+                 float* dg_part, hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
+  MArgs g{};
+  g.A0 = (const bf16_t*)dys; g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = ga;
+  g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3; g.gates = gates; g.perm = perm; g.dg_part = dg_part;
+  g.n_part = mfma_bwd_act_partials(sh.f);
+  g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
+  g.strideB_e = sh.s2; g.R = sh.R;
+  return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 2, BWD_ACT>(g, s)
+                        : launch<256, kActBN, 32, 2, 4, 4, BWD_ACT>(g, s);
+}
+
+int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
+                const FfShapes& sh, void* dxs, hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
+  MArgs g{};
+  g.A0 = (const bf16_t*)dh1; g.A1 = (const bf16_t*)dh3; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = dxs;
+  g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.f; g.ldc = sh.d;
+  g.strideB_e = sh.s13; g.R = sh.R;
+  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, BWD_DX>(g, s);
+}
+
+int mfma_bwd_dw(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga, const void* dys,
+                const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2, hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
+  MArgs g{};
+  g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
+  g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
+  g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
+  if (int rc = launch<256, 256, 64, 2, 4, 2, DW13>(g, s)) return rc;
+  MArgs h{};
+  h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dys; h.C0 = dW2;
+  h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = sh.d; h.ldc = sh.d;
+  h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
+  return launch<256, 256, 64, 2, 4, 2, DW2>(h, s);
+}
+
+}  // namespace btx
