@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE feed-forward layer (route -> forward -> backward) on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch that is already
+resident in HBM: btx_moe_route, btx_moe_ff_forward (saving h1/h3) and
+btx_moe_ff_backward (dX, dW_router, db_router, dW1/dW3/dW2, load-balancing gradient).
+Prints ONE JSON line: layer tokens/s, the MFMA roofline of the dominant expert-GEMM
+kernel (timed live with HIP events recorded inside the library around every stage), and
+the CPU oracle timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2403_07816_amd import binding as B  # noqa: E402
+from paper_2403_07816_amd import synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
+WORKLOAD = dict(name="llama2-7b-shaped MoE-FF layer, fwd+bwd, T=16384 (4 seq x 4096), d=4096, f=11008, E=4, top-2, "
+                     "bf16, load-balancing loss alpha=0.01",
+                T=16384, d=4096, f=11008, E=4, k=2, alpha=0.01)
+GEMM_STAGES = {"up_swiglu": 4, "down": 2, "bwd_act": 2, "bwd_dx": 4, "dw13": 4, "dw2": 2}   # x d*f*R flops
+
+
+class HipEvents:
+    """Raw hipEvent_t handles (the library records them on the stream it launches on)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.ev = (ctypes.c_void_p * n)()
+        for i in range(n):
+            e = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+            self.ev[i] = e.value
+
+    def slice(self, start, count):
+        return ctypes.cast(ctypes.byref(self.ev, start * ctypes.sizeof(ctypes.c_void_p)),
+                           ctypes.POINTER(ctypes.c_void_p)), count
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(self.ev[a]), ctypes.c_void_p(self.ev[b]))
+        return ms.value if rc == 0 else float("nan")
+
+
+def cpu_baseline(L, W, sample_tokens):
+    """The oracle, as it stands, on the first `sample_tokens` tokens of the batch."""
+    from oracle import btx_oracle as O
+    f64 = lambda t: None if t is None else t.detach().float().cpu().numpy().astype(np.float64)
+    x, dY = f64(L["x"][:sample_tokens]), f64(L["dY"][:sample_tokens])
+    Wr = f64(L["W_router"])
+    W1 = [f64(L["W1"][e]) for e in range(W["E"])]
+    W3 = [f64(L["W3"][e]) for e in range(W["E"])]
+    W2 = [f64(L["W2"][e]) for e in range(W["E"])]
+    t0 = time.perf_counter()
+    fwd = O.moe_forward(x, Wr, None, W1, W3, W2, W["k"], O.ROUTE_TOPK_RENORM, None, W["alpha"], O.LB_TOKEN_FRAC)
+    O.moe_backward(x, Wr, None, W1, W3, W2, W["k"], O.ROUTE_TOPK_RENORM, dY, fwd, W["alpha"], O.LB_TOKEN_FRAC, 1.0)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {sample_tokens} tokens of the same batch, fwd+bwd in fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tokens", type=int, default=WORKLOAD["T"], help="override T (parity/dev runs only)")
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    W = dict(WORKLOAD)
+    W["T"] = args.tokens
+    T, d, f, E, k, alpha = W["T"], W["d"], W["f"], W["E"], W["k"], W["alpha"]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    L = synth.make_layer(T, d, f, E, dtype=torch.bfloat16, device=dev, unit_rms=True, with_dY=True)
+    lib = B.load_library()
+
+    # everything a step writes is allocated once, outside the timed region
+    routing = B.alloc_routing(T, E, k, dev)
+    out = torch.empty_like(L["x"])
+    saved = (torch.empty((T * k, f), dtype=torch.bfloat16, device=dev),
+             torch.empty((T * k, f), dtype=torch.bfloat16, device=dev))
+    grads = B.Grads(torch.empty_like(L["x"]), torch.empty((d, E), dtype=torch.float32, device=dev),
+                    torch.empty(E, dtype=torch.float32, device=dev), torch.empty_like(L["W1"]),
+                    torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
+    ws_bytes = max(lib.btx_moe_route_workspace_bytes(T, E, k),
+                   lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
+                   lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        B.btx_moe_route(L["x"], L["W_router"], None, None, k, B.BTX_ROUTE_TOPK_RENORM, B.BTX_LB_TOKEN_FRAC, alpha,
+                        out=routing, workspace=ws)
+        B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, save=True, out=out, saved=saved, workspace=ws)
+        B.btx_moe_ff_backward(L["dY"], L["x"], L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
+                              B.BTX_ROUTE_TOPK_RENORM, B.BTX_LB_TOKEN_FRAC, alpha, 1.0, 0, out=grads, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    n_stage = len(B.STAGE_NAMES)
+    events = HipEvents(2 * n_stage * args.steps)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ptr, n = events.slice(2 * n_stage * s, n_stage)
+        lib.btx_profile_stages(ptr, n)
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    lib.btx_profile_stages(None, 0)
+
+    stage_ms = {}
+    for i, name in enumerate(B.STAGE_NAMES):
+        v = [events.elapsed_ms(2 * n_stage * s + 2 * i, 2 * n_stage * s + 2 * i + 1) for s in range(args.steps)]
+        stage_ms[name] = float(np.mean(v))
+    R = T * k
+    gemm = {n: {"ms": stage_ms[n], "tflops": c * d * f * R / (stage_ms[n] * 1e-3) / 1e12} for n, c in GEMM_STAGES.items()}
+    dominant = max(gemm, key=lambda n: gemm[n]["ms"])
+    gemm_ms = sum(v["ms"] for v in gemm.values())
+    gemm_tflops = 18.0 * d * f * R / (gemm_ms * 1e-3) / 1e12
+
+    ms_per_step = elapsed / args.steps * 1e3
+    result = {
+        "metric": "MoE-FF layer tokens/s fwd+bwd (d4096,f11008,E4,top2)",
+        "value": T * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": W["name"] if T == WORKLOAD["T"] else f"dev run, T={T}", "tokens": T, "d_model": d,
+                   "d_ff": f, "experts": E, "top_k": k},
+        "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm[dominant]["tflops"] / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+        "expert_gemms": {"ms": gemm_ms, "tflops": gemm_tflops, "frac_of_peak": gemm_tflops / PEAK_BF16_TFLOPS,
+                         "layer_frac_of_peak": 18.0 * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                         "per_kernel": gemm},
+        "stage_ms": stage_ms,
+    }
+    if args.cpu_sample > 0:
+        result["cpu_baseline"] = cpu_baseline(L, W, min(args.cpu_sample, T))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

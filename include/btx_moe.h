@@ -73,6 +73,28 @@ typedef enum {
 const char* btx_status_string(int status);
 int btx_version(void);
 
+/* Profiling aid (the one piece of process-wide state; not thread-safe; off by default).
+ * events: HOST array of 2*n_pairs hipEvent_t handles owned by the caller.  While set,
+ * stage s of any later call records events[2s] before and events[2s+1] after its
+ * kernels on the caller's stream, so that single kernels can be timed inside the real
+ * sequence.  n_pairs = 0 switches it off.  Stage ids: */
+enum {
+  BTX_STAGE_ROUTE = 0,        /* btx_moe_route: all three kernels                  */
+  BTX_STAGE_GATHER_X = 1,     /* forward: x -> expert-grouped rows                 */
+  BTX_STAGE_UP = 2,           /* forward: xs W1, xs W3, SwiGLU                     */
+  BTX_STAGE_DOWN = 3,         /* forward: act W2                                   */
+  BTX_STAGE_COMBINE = 4,      /* forward: gate-weighted un-permute                 */
+  BTX_STAGE_GATHER_DY = 5,    /* backward: dY -> grouped rows                      */
+  BTX_STAGE_BWD_ACT = 6,      /* backward: dys W2^T + SwiGLU backward              */
+  BTX_STAGE_BWD_DX = 7,       /* backward: dh1 W1^T + dh3 W3^T                     */
+  BTX_STAGE_GATHER_X_BWD = 8, /* backward: x -> grouped rows (for dW1, dW3)        */
+  BTX_STAGE_DW13 = 9,         /* backward: dW1, dW3                                */
+  BTX_STAGE_DW2 = 10,         /* backward: dW2                                     */
+  BTX_STAGE_ROUTER_BWD = 11,  /* backward: router gradients and final dX           */
+  BTX_STAGE_COUNT = 12
+};
+int btx_profile_stages(void** events, int n_pairs);
+
 /* ---------------------------------------------------------------------------
  * btx_moe_route - router linear, softmax, selection, gates, load-balancing
  * statistics and the token -> expert grouping (Sec. 3.2: W_l x and

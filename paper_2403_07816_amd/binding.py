@@ -17,6 +17,8 @@ BTX_F32, BTX_BF16 = 0, 1
 BTX_ROUTE_TOPK_RENORM, BTX_ROUTE_SWITCH_TOP1, BTX_ROUTE_SAMPLE_TOP1 = 0, 1, 2
 BTX_LB_TOKEN_FRAC, BTX_LB_GATE_MEAN = 0, 1
 BTX_FLAG_LB_GRAD_THROUGH_U = 1
+STAGE_NAMES = ["route", "gather_x", "up_swiglu", "down", "combine", "gather_dy", "bwd_act", "bwd_dx", "gather_x_bwd",
+               "dw13", "dw2", "router_bwd"]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbtx_moe.so")
 _lib = None
@@ -26,6 +28,7 @@ _vp, _i, _i64, _f, _sz, _u = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, cty
 _SIGNATURES = {
     "btx_status_string": (ctypes.c_char_p, [_i]),
     "btx_version": (_i, []),
+    "btx_profile_stages": (_i, [ctypes.POINTER(_vp), _i]),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),

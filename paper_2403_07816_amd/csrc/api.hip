@@ -51,6 +51,26 @@ BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   return w;
 }
 
+// Optional profiling aid: when set, every stage of the layer is bracketed by a pair of
+// events recorded on the caller's stream (see btx_profile_stages in the header).
+hipEvent_t* g_stage_events = nullptr;
+int g_stage_event_pairs = 0;
+
+struct StageTimer {
+  int id; hipStream_t s;
+  StageTimer(int id_, hipStream_t s_) : id(id_), s(s_) {
+    if (g_stage_events && id < g_stage_event_pairs) (void)hipEventRecord(g_stage_events[2 * id], s);
+  }
+  ~StageTimer() {
+    if (g_stage_events && id < g_stage_event_pairs) (void)hipEventRecord(g_stage_events[2 * id + 1], s);
+  }
+};
+#define BTX_STAGE(id, call)            \
+  do {                                 \
+    StageTimer timer_(id, s);          \
+    if (int rc_ = (call)) return rc_;  \
+  } while (0)
+
 bool shapes_ok(int T, int d, int f, int E, int k) {
   return T >= 0 && d > 0 && f > 0 && E >= 1 && E <= kMaxExperts && k >= 1 && k <= E && d % 8 == 0 && f % 8 == 0 &&
          (int64_t)T * k < (int64_t)1 << 31 && (int64_t)T * k * (int64_t)(d > f ? d : f) < (int64_t)1 << 40;
@@ -73,6 +93,13 @@ const char* btx_status_string(int status) {
 }
 
 int btx_version(void) { return 1; }
+
+int btx_profile_stages(void** events, int n_pairs) {
+  if (n_pairs < 0 || (n_pairs > 0 && !events)) return BTX_ERR_INVALID_ARG;
+  g_stage_events = n_pairs ? reinterpret_cast<hipEvent_t*>(events) : nullptr;
+  g_stage_event_pairs = n_pairs;
+  return BTX_OK;
+}
 
 size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
   if (T <= 0 || E < 1 || E > kMaxExperts || k < 1 || k > E) return 0;
@@ -97,7 +124,9 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
   if (workspace_bytes < route_workspace_bytes(T, E, k)) return BTX_ERR_WORKSPACE;
   RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, topk_idx, gates, probs,
               counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace};
-  return launch_route(a, static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  BTX_STAGE(BTX_STAGE_ROUTE, launch_route(a, s));
+  return BTX_OK;
 }
 
 size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int dtype) {
@@ -122,10 +151,11 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
   void* h1 = save_h1 ? save_h1 : w.h1;
   void* h3 = save_h3 ? save_h3 : w.h3;
-  if (int rc = launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s)) return rc;
-  if (int rc = launch_up_swiglu(dtype, w.xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s)) return rc;
-  if (int rc = launch_down(dtype, w.act, W2, offsets, sh, w.y, s)) return rc;
-  return launch_combine(w.y, gates, inv_pos, out, T, k, d, dtype, s);
+  BTX_STAGE(BTX_STAGE_GATHER_X, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
+  BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, w.xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
+  BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, s));
+  BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, out, T, k, d, dtype, s));
+  return BTX_OK;
 }
 
 size_t btx_moe_ff_backward_workspace_bytes(int T, int d, int f, int E, int k, int dtype) {
@@ -160,20 +190,20 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int R = T * k;
   const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
-  if (int rc = launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s)) return rc;
-  if (int rc = launch_bwd_act(dtype, w.dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1, w.dh3, w.ga,
-                              w.dg_part, w.scratch, s))
-    return rc;
-  if (int rc = launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s)) return rc;
+  BTX_STAGE(BTX_STAGE_GATHER_DY, launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s));
+  BTX_STAGE(BTX_STAGE_BWD_ACT, launch_bwd_act(dtype, w.dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1,
+                                              w.dh3, w.ga, w.dg_part, w.scratch, s));
+  BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s));
   if (n_dw == 3) {
-    if (int rc = launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s)) return rc;
-    if (int rc = launch_bwd_dw(dtype, dW_dtype, w.xs, w.dh1, w.dh3, w.ga, w.dys, offsets, sh, dW1, dW3, dW2, s))
-      return rc;
+    BTX_STAGE(BTX_STAGE_GATHER_X_BWD, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
+    BTX_STAGE(BTX_STAGE_DW13, launch_bwd_dw13(dtype, dW_dtype, w.xs, w.dh1, w.dh3, offsets, sh, dW1, dW3, s));
+    BTX_STAGE(BTX_STAGE_DW2, launch_bwd_dw2(dtype, dW_dtype, w.ga, w.dys, offsets, sh, dW2, s));
   }
   RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, topk_idx,
                    gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,
                    dW_router, db_router, w.router};
-  return launch_router_bwd(ra, s);
+  BTX_STAGE(BTX_STAGE_ROUTER_BWD, launch_router_bwd(ra, s));
+  return BTX_OK;
 }
 
 int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, void* stream) {

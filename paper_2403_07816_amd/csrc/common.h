@@ -113,9 +113,10 @@ int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, c
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
                   const FfShapes& sh, void* dxs, hipStream_t s);
 // dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows
-int launch_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
-                  const void* dys, const int32_t* offsets, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
-                  hipStream_t s);
+int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* offsets,
+                    const FfShapes& sh, void* dW1, void* dW3, hipStream_t s);
+int launch_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* offsets, const FfShapes& sh,
+                   void* dW2, hipStream_t s);
 size_t ff_scratch_bytes(int dtype, int R, int f);
 
 struct RouterBwdArgs {

@@ -38,11 +38,15 @@ int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, c
   if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dx(dh1, dh3, W1, W3, offsets, sh, dxs, s);
   return generic_bwd_dx(dtype, dh1, dh3, W1, W3, offsets, sh, dxs, s);
 }
-int launch_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
-                  const void* dys, const int32_t* offsets, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
-                  hipStream_t s) {
-  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dw(dW_dtype, xs, dh1, dh3, ga, dys, offsets, sh, dW1, dW3, dW2, s);
-  return generic_bwd_dw(dtype, dW_dtype, xs, dh1, dh3, ga, dys, offsets, sh, dW1, dW3, dW2, s);
+int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* offsets,
+                    const FfShapes& sh, void* dW1, void* dW3, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dw13(dW_dtype, xs, dh1, dh3, offsets, sh, dW1, dW3, s);
+  return generic_bwd_dw13(dtype, dW_dtype, xs, dh1, dh3, offsets, sh, dW1, dW3, s);
+}
+int launch_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* offsets, const FfShapes& sh,
+                   void* dW2, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dw2(dW_dtype, ga, dys, offsets, sh, dW2, s);
+  return generic_bwd_dw2(dtype, dW_dtype, ga, dys, offsets, sh, dW2, s);
 }
 
 }  // namespace btx

@@ -12,7 +12,8 @@ int generic_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, 
                     float* dg_part, void* scratch, hipStream_t s);
 int generic_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
                    const FfShapes& sh, void* dxs, hipStream_t s);
-int generic_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
-                   const void* dys, const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
-                   hipStream_t s);
+int generic_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
+                     const FfShapes& sh, void* dW1, void* dW3, hipStream_t s);
+int generic_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh,
+                    void* dW2, hipStream_t s);
 }  // namespace btx

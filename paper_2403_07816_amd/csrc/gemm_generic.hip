@@ -186,17 +186,21 @@ struct Generic {
     return run<ET, ET, ET>(g, sh.R, s);
   }
   template <typename WT>
-  static int bwd_dw(const void* xs, const void* dh1, const void* dh3, const void* ga, const void* dys,
-                    const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2, hipStream_t s) {
+  static int bwd_dw13(const void* xs, const void* dh1, const void* dh3, const int32_t* off, const FfShapes& sh,
+                      void* dW1, void* dW3, hipStream_t s) {
     GArgs g{};  // dW1[m,c] = sum_r xs[r,m] dh1[r,c]
     g.A = xs; g.sam = 1; g.sak = sh.d; g.B = dh1; g.sbk = sh.f; g.sbn = 1; g.C = dW1; g.ldc = sh.f; g.M = sh.d;
     g.N = sh.f; g.offsets = off; g.E = sh.E; g.strideC_e = sh.s13; g.group_mode = GROUP_K;
     if (int rc = run<ET, ET, WT>(g, sh.R, s)) return rc;
     g.B = dh3; g.C = dW3;
-    if (int rc = run<ET, ET, WT>(g, sh.R, s)) return rc;
-    // dW2[c,m] = sum_r ga[r,c] dys[r,m]
+    return run<ET, ET, WT>(g, sh.R, s);
+  }
+  template <typename WT>
+  static int bwd_dw2(const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW2,
+                     hipStream_t s) {
+    GArgs g{};  // dW2[c,m] = sum_r ga[r,c] dys[r,m]
     g.A = ga; g.sam = 1; g.sak = sh.f; g.B = dys; g.sbk = sh.d; g.sbn = 1; g.C = dW2; g.ldc = sh.d; g.M = sh.f;
-    g.N = sh.d; g.strideC_e = sh.s2;
+    g.N = sh.d; g.offsets = off; g.E = sh.E; g.strideC_e = sh.s2; g.group_mode = GROUP_K;
     return run<ET, ET, WT>(g, sh.R, s);
   }
 };
@@ -224,15 +228,21 @@ int generic_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, 
   return dtype == BTX_BF16 ? Generic<bf16_t>::bwd_dx(dh1, dh3, W1, W3, off, sh, dxs, s)
                            : Generic<float>::bwd_dx(dh1, dh3, W1, W3, off, sh, dxs, s);
 }
-int generic_bwd_dw(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga,
-                   const void* dys, const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2,
-                   hipStream_t s) {
+int generic_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
+                     const FfShapes& sh, void* dW1, void* dW3, hipStream_t s) {
   if (dtype == BTX_BF16) {
-    return dW_dtype == BTX_BF16
-               ? Generic<bf16_t>::bwd_dw<bf16_t>(xs, dh1, dh3, ga, dys, off, sh, dW1, dW3, dW2, s)
-               : Generic<bf16_t>::bwd_dw<float>(xs, dh1, dh3, ga, dys, off, sh, dW1, dW3, dW2, s);
+    return dW_dtype == BTX_BF16 ? Generic<bf16_t>::bwd_dw13<bf16_t>(xs, dh1, dh3, off, sh, dW1, dW3, s)
+                                : Generic<bf16_t>::bwd_dw13<float>(xs, dh1, dh3, off, sh, dW1, dW3, s);
   }
-  return Generic<float>::bwd_dw<float>(xs, dh1, dh3, ga, dys, off, sh, dW1, dW3, dW2, s);
+  return Generic<float>::bwd_dw13<float>(xs, dh1, dh3, off, sh, dW1, dW3, s);
+}
+int generic_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh,
+                    void* dW2, hipStream_t s) {
+  if (dtype == BTX_BF16) {
+    return dW_dtype == BTX_BF16 ? Generic<bf16_t>::bwd_dw2<bf16_t>(ga, dys, off, sh, dW2, s)
+                                : Generic<bf16_t>::bwd_dw2<float>(ga, dys, off, sh, dW2, s);
+  }
+  return Generic<float>::bwd_dw2<float>(ga, dys, off, sh, dW2, s);
 }
 
 }  // namespace btx

@@ -489,14 +489,19 @@ int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3
   return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, BWD_DX>(g, s);
 }
 
-int mfma_bwd_dw(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const void* ga, const void* dys,
-                const int32_t* off, const FfShapes& sh, void* dW1, void* dW3, void* dW2, hipStream_t s) {
+int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
+                  const FfShapes& sh, void* dW1, void* dW3, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
   g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
-  if (int rc = launch<256, 256, 64, 2, 4, 2, DW13>(g, s)) return rc;
+  return launch<256, 256, 64, 2, 4, 2, DW13>(g, s);
+}
+
+int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW2,
+                 hipStream_t s) {
+  if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs h{};
   h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dys; h.C0 = dW2;
   h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = sh.d; h.ldc = sh.d;
