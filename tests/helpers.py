@@ -59,21 +59,29 @@ def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False):
                          forced_idx=forced, keep_y=keep_y)
 
 
-def check_route(r: B.Routing, L, k, mode, alpha, lb_mode):
-    """Compare btx_moe_route's outputs with the oracle; returns the oracle forward
-    result (with near-tie rows forced to the GPU's choice)."""
+def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True):
+    """Compare btx_moe_route's outputs with the oracle.  Returns the oracle's forward
+    result (near-tie rows forced to the GPU's choice); with full_forward=False only the
+    routing part and the statistics are evaluated (what full-size tests can afford)."""
     E = L["W_router"].shape[1]
     U = to_np(L["U"])
+    x, Wr, b = to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"])
     idx_gpu = r.topk_idx.cpu().numpy().astype(np.int64)
-    orc = O.route(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), k, mode, U)
+    orc = O.route(x, Wr, b, k, mode, U)
     forced, n_forced = reconcile_routing(idx_gpu, orc, mode, U)
     assert n_forced <= max(1, idx_gpu.shape[0] // 1000), f"{n_forced} near-tie rows is implausibly many"
-    fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True)
+    if full_forward:
+        fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True)
+    else:
+        fwd = O.route(x, Wr, b, k, mode, U, forced_idx=forced) if n_forced else orc
+        fwd.update(O.lb_statistics(fwd["idx"], fwd["gates"], fwd["probs"], alpha, lb_mode))
+    fwd["n_forced"] = n_forced
     assert np.array_equal(fwd["idx"], idx_gpu)
     assert_close(r.gates.cpu().numpy(), fwd["gates"], ROUTER_TOL, "gates")
     assert_close(r.probs.cpu().numpy(), fwd["probs"], ROUTER_TOL, "probs")
     assert np.array_equal(r.counts.cpu().numpy(), fwd["counts"]), "counts"
     grp = O.grouping(fwd["idx"], E)
+    fwd.update(grp)
     assert np.array_equal(r.offsets.cpu().numpy(), grp["offsets"]), "offsets"
     assert np.array_equal(r.perm.cpu().numpy(), grp["perm"]), "perm"
     assert np.array_equal(r.inv_pos.cpu().numpy(), grp["inv_pos"]), "inv_pos"
