@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tokens", type=int, default=WORKLOAD["T"], help="override T (parity/dev runs only)")
-    ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
