@@ -27,6 +27,24 @@
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
 
+#ifndef BTX_SUP_M
+#define BTX_SUP_M 16   // supertile: row tiles x column tiles that run concurrently chip-wide
+#define BTX_SUP_N 16
+#define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
+#endif
+#ifndef BTX_SETPRIO
+#define BTX_SETPRIO 1
+#endif
+#ifndef BTX_PINGPONG
+#define BTX_PINGPONG 1
+#endif
+#ifndef BTX_ISSUE_PARTS
+#define BTX_ISSUE_PARTS 1   // k steps over which the copies of the next tile are spread (1 = all at once)
+#endif
+#ifndef BTX_EXP
+#define BTX_EXP 0   // dev experiments only (bit 0: no global copies, bit 1: no LDS reads, bit 2: no MFMA)
+#endif
+
 namespace btx {
 namespace {
 
@@ -102,7 +120,10 @@ struct Gemm {
 
   // ---- LDS addressing ----------------------------------------------------
   // K-contiguous tile: [rows][BK], 16-byte chunks XOR-swizzled by row
-  static __device__ __forceinline__ int kc_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  static __device__ __forceinline__ int kc_swz(int row) {
+    if (BTX_EXP & 16) return 0;
+    return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+  }
   // strided-K tile: [BK][COLS], 16-byte chunk index XORed with (k & 3) << 2
 
   // byte offset inside a wave's copy `seg` (1 KB each) -> global element offset, for both layouts
@@ -119,7 +140,7 @@ struct Gemm {
       const int k = o / PITCH;
       const int phys = (o % PITCH) / 16;
       major = k;                                // k row of the tile
-      minor_elem = (phys ^ ((k & 3) << 2)) * 8; // column offset inside the tile
+      minor_elem = (phys ^ ((BTX_EXP & 32) ? 0 : ((k & 3) << 2))) * 8; // column offset inside the tile
     }
   }
 
@@ -146,28 +167,27 @@ struct Gemm {
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- which tile ------------------------------------------------------
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
-    // tile ids so that tiles sharing operand panels meet in one L2, then walk the range in
-    // groups of kGroupM row tiles x all column tiles.
-    const int total = g.tiles_m * g.tiles_n * (GROUP_K ? g.E : 1);
+    // Workgroups are dealt round-robin to the 8 XCDs (block id mod 8) and start in id order.
+    // kSupM x kSupN consecutive ids form one supertile of the tile grid, so that the tiles
+    // running at any moment share few operand panels chip-wide (little HBM / infinity-cache
+    // traffic, short miss latency); inside it XCD x owns a (kSupM/kXcdM) x (kSupN/kXcdN)
+    // sub-block, so that the panels its CUs stream meet in that XCD's L2.
+    constexpr int kSupM = BTX_SUP_M, kSupN = BTX_SUP_N, kXcdM = BTX_XCD_M, kXcdN = 8 / kXcdM;
+    constexpr int kSubM = kSupM / kXcdM, kSubN = kSupN / kXcdN;
+    static_assert(kSubM * kXcdM == kSupM && kSubN * kXcdN == kSupN, "supertile must split over 8 XCDs");
+    const int sup_n = (g.tiles_n + kSupN - 1) / kSupN, sup_m = (g.tiles_m + kSupM - 1) / kSupM;
     int id = blockIdx.x;
-    {
-      const int per = total / 8, rem = total % 8, x = id % 8, q = id / 8;
-      // XCD x owns per (+1 if x < rem) ids starting at x*per + min(x, rem)
-      id = x * per + (x < rem ? x : rem) + q;
-    }
     int e = 0;
     if (GROUP_K) {
-      const int per_e = g.tiles_m * g.tiles_n;
+      const int per_e = sup_m * sup_n * (kSupM * kSupN);
       e = id / per_e;
       id -= e * per_e;
     }
-    constexpr int kGroupM = 4;
-    const int gsz = kGroupM * g.tiles_n;
-    const int grp = id / gsz, in = id % gsz;
-    const int m_first = grp * kGroupM;
-    const int m_cnt = min(kGroupM, g.tiles_m - m_first);
-    const int tile_m = m_first + in % m_cnt, tile_n = in / m_cnt;
+    const int sup = id / (kSupM * kSupN), r = id % (kSupM * kSupN);
+    const int xcd = r % 8, slot = r / 8;
+    const int tile_m = (sup / sup_n) * kSupM + (xcd % kXcdM) * kSubM + slot % kSubM;
+    const int tile_n = (sup % sup_n) * kSupN + (xcd / kXcdM) * kSubN + slot / kSubM;
+    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
 
     int row0, row_end, k_begin, k_end;
     if (GROUP_K) {
@@ -231,27 +251,33 @@ struct Gemm {
     const int nk = MODE == BWD_DX ? 2 * nk1 : nk1;
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
 
-    auto issue = [&](int kt) {
+    // Copies of tile kt; part p of nparts issues every nparts-th copy, so that the copies can
+    // be spread between the MFMA groups of the tile being computed instead of stalling every
+    // wavefront at the top of the iteration while the address unit drains them.
+    auto issue = [&](int kt, int part, int nparts) {
+      if (BTX_EXP & 1) return;
       const uint32_t stage = smem_base + (kt % NSTAGE) * STAGE_BYTES;
       const bool pass2 = MODE == BWD_DX && kt >= nk1;
       const int k0 = k_begin + (pass2 ? kt - nk1 : kt) * BK;
       const bf16_t* Ab = pass2 ? g.A1 : g.A0;
-      Ab += A_KC ? (size_t)row0 * g.lda + k0 : (size_t)k0 * g.lda;
-#pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) {
-        uint32_t off = a_off[q];
-        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
-        if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
-        copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
-      }
-      const bf16_t* B0b = Bp0 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
+      Ab += A_KC ? (size_t)((BTX_EXP & 8) ? 0 : row0) * g.lda + k0 : (size_t)k0 * g.lda;
+      const bf16_t* B0b = ((BTX_EXP & 8) ? g.B0 : Bp0) + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
       const bf16_t* B1b = Bp1 ? Bp1 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb) : nullptr;
 #pragma unroll
-      for (int q = 0; q < B_LOADS; ++q) {
-        uint32_t off = b_off[q];
-        if (GROUP_K) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
-        const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[q]);
-        copy16_to_lds(second ? B1b : B0b, off, stage + A_BYTES + (wave * B_LOADS + q) * 1024);
+      for (int q = 0; q < A_LOADS + B_LOADS; ++q) {
+        if (q % nparts != part) continue;
+        if (q < A_LOADS) {
+          uint32_t off = a_off[q];
+          // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
+          if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
+          copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
+        } else {
+          const int qb = q - A_LOADS;
+          uint32_t off = b_off[qb];
+          if (GROUP_K) off = (uint32_t)((min(k0 + b_k[qb], g.R - 1) - k0) * g.ldb + b_c[qb]) * 2u;
+          const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[qb]);
+          copy16_to_lds(second ? B1b : B0b, off, stage + A_BYTES + (wave * B_LOADS + qb) * 1024);
+        }
       }
     };
 
@@ -266,49 +292,161 @@ struct Gemm {
     constexpr int PER_TILE = A_LOADS + B_LOADS;
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
-      if (s < nk) issue(s);
+      if (s < nk) issue(s, 0, 1);
 
-    for (int kt = 0; kt < nk; ++kt) {
-      // tile kt must have landed; up to NSTAGE-2 younger tiles may still be in flight
+    auto load_frags = [&](const char* At, const char* Bt, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = wm * (TM * 32) + i * 32;
+        if (BTX_EXP & 2) { for (int x = 0; x < 8; ++x) af[i][x] = (__bf16)(float)(lane + i); continue; }
+        af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int c = wn * (TNH * 32) + (j % TNH) * 32;
+        if (BTX_EXP & 2) { for (int x = 0; x < 8; ++x) bfr[j][x] = (__bf16)(float)(lane + j); continue; }
+        bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
+      }
+    };
+
+    unsigned long long dbg_wait = 0, dbg_bar = 0, dbg_t0 = 0;
+    if (BTX_EXP & 128) dbg_t0 = __builtin_readcyclecounter();
+
+    // Wait until tile kt has landed (up to NSTAGE-2 younger tiles may stay in flight) and
+    // publish it; passing the barrier also means every wavefront is done reading tile kt-1.
+    const bool tracing = (BTX_EXP & 256) && blockIdx.x == 300 && g.dg_part != nullptr;
+    auto trace = [&](int kt, int slot) {
+      if ((BTX_EXP & 256) && tracing && kt >= 60 && kt < 64 && lane == 0)
+        reinterpret_cast<unsigned long long*>(g.dg_part)[((kt - 60) * NW + wave) * 8 + slot] = __builtin_readcyclecounter();
+    };
+    auto publish = [&](int kt) {
+      unsigned long long c0 = 0, c1 = 0;
+      trace(kt - 1, 4);
+      if (BTX_EXP & 128) c0 = __builtin_readcyclecounter();
       if (kt + NSTAGE - 2 < nk) wait_vmcnt((NSTAGE - 2) * PER_TILE);
       else wait_vmcnt(0);
-      __syncthreads();
-      if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+      if (BTX_EXP & 128) c1 = __builtin_readcyclecounter();
+      trace(kt - 1, 5);
+      if (!(BTX_EXP & 64)) __syncthreads();
+      trace(kt, 0);
+      if (BTX_EXP & 128) { const unsigned long long c2 = __builtin_readcyclecounter(); dbg_wait += c1 - c0; dbg_bar += c2 - c1; }
+    };
+    auto mfma_step = [&](bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          if (BTX_EXP & 4) { acc[i][j][0] += (float)af[i][0] * (float)bfr[j][0]; }
+          else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    };
+    // grouped-K: rows past the expert's last one belong to the next expert; zero A there
+    auto zero_tail = [&](int kt, int ks, bf16x8 (&af)[TM]) {
+      const int kb = kt * BK + ks * 16 + 8 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+          if (kb + x >= k_len) af[i][x] = (__bf16)0.0f;
+    };
 
-      const char* stage = smem + (kt % NSTAGE) * STAGE_BYTES;
-      const char* At = stage;
-      const char* Bt = stage + A_BYTES;
-      const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        bf16x8 af[TM], bfr[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int r = wm * (TM * 32) + i * 32;
-          af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
-        }
-        if (k_tail) {
-          // grouped-K: rows past the expert's last one belong to the next expert; zero A there
-          const int kb = kt * BK + ks * 16 + 8 * (lane >> 5);
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int x = 0; x < 8; ++x)
-              if (kb + x >= k_len) af[i][x] = (__bf16)0.0f;
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int c = wn * (TNH * 32) + (j % TNH) * 32;
-          bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    if (BTX_PINGPONG && NW == 8 && NSTAGE == 2 && KSTEPS % 2 == 0) {
+      // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) alternate
+      // between a memory phase (LDS fragment reads + the global->LDS copies of the next
+      // tile) and a compute phase (an uninterrupted run of MFMAs), half a period apart and
+      // kept in step by a barrier at every phase boundary.  The matrix pipe always has one
+      // wavefront feeding it and is never held up behind a wavefront that is stuck issuing
+      // copies or waiting for LDS.
+      constexpr int HS = KSTEPS / 2;                 // k steps per half tile
+      const int grp = BTX_PINGPONG == 2 ? (wave & 1) : wave / (NW / 2);   // group 1 lags group 0 by one phase
+      bf16x8 fa[HS][TM], fb[HS][TN];
+      if (nk > 0) {
+        wait_vmcnt(0);
+        __builtin_amdgcn_s_barrier();                // tile 0 published
       }
+      if (grp == 1) __builtin_amdgcn_s_barrier();    // idle during group 0's first memory phase
+      unsigned long long tm = 0, tb1 = 0, tc = 0, tv = 0, tb2 = 0;   // BTX_EXP & 128: phase timers
+      auto now = [&]() -> unsigned long long { return (BTX_EXP & 128) ? __builtin_readcyclecounter() : 0ull; };
+      for (int kt = 0; kt < nk; ++kt) {
+        const char* At = smem + (kt % NSTAGE) * STAGE_BYTES;
+        const char* Bt = At + A_BYTES;
+        const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          // ---- memory phase
+          const unsigned long long t0 = now();
+#pragma unroll
+          for (int x = 0; x < HS; ++x) load_frags(At, Bt, h * HS + x, fa[x], fb[x]);
+          if (h == 0 && kt + 1 < nk) issue(kt + 1, 0, 1);
+          if (k_tail) {
+#pragma unroll
+            for (int x = 0; x < HS; ++x) zero_tail(kt, h * HS + x, fa[x]);
+          }
+          __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): fragments are in registers
+          const unsigned long long t1 = now();
+          if (h == 1 && grp == 1) wait_vmcnt(0);     // group 1's copies of tile kt+1 have landed
+          const unsigned long long t2 = now();
+          __builtin_amdgcn_sched_barrier(0);
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          const unsigned long long t3 = now();
+          // ---- compute phase
+          if (BTX_SETPRIO) __builtin_amdgcn_s_setprio(BTX_SETPRIO);
+#pragma unroll
+          for (int x = 0; x < HS; ++x) mfma_step(fa[x], fb[x]);
+          if (BTX_SETPRIO) __builtin_amdgcn_s_setprio(0);
+          const unsigned long long t4 = now();
+          if (h == 1 && grp == 0) wait_vmcnt(0);     // group 0's copies of tile kt+1 have landed
+          const unsigned long long t5 = now();
+          __builtin_amdgcn_sched_barrier(0);
+          if (!(grp == 1 && h == 1 && kt + 1 == nk)) __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+          const unsigned long long t6 = now();
+          tm += t1 - t0; tv += (t2 - t1) + (t5 - t4); tb1 += t3 - t2; tc += t4 - t3; tb2 += t6 - t5;
+        }
+      }
+      if ((BTX_EXP & 128) && lane == 0 && g.dg_part) {
+        float* o = g.dg_part + ((size_t)blockIdx.x * NW + wave) * 8;
+        o[0] = (float)tm; o[1] = (float)tb1; o[2] = (float)tc; o[3] = (float)tb2; o[4] = (float)tv; o[5] = (float)nk;
+      }
+    } else {
+    // The loop is rotated by one k step: the MFMAs of a tile's last k step run after the
+    // barrier that publishes the next tile, right behind the LDS reads of that tile's first
+    // fragments, so the matrix pipe has work while those reads are in flight.
+    static_assert(KSTEPS % 2 == 0, "fragment double buffer assumes an even number of k steps");
+    bf16x8 af[2][TM], bfr[2][TN];
+    if (nk > 0) {
+      publish(0);
+      load_frags(smem, smem + A_BYTES, 0, af[0], bfr[0]);
+    }
+    for (int kt = 0; kt < nk; ++kt) {
+      const char* At = smem + (kt % NSTAGE) * STAGE_BYTES;
+      const char* Bt = At + A_BYTES;
+      const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
+      // the stage of tile kt+NSTAGE-1 was last read for tile kt-1: free since the last barrier
+      const bool prefetch = kt + NSTAGE - 1 < nk;
+#pragma unroll
+      for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
+        const int cur = ks & 1;
+        load_frags(At, Bt, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+        if (prefetch) issue(kt + NSTAGE - 1, ks, BTX_ISSUE_PARTS);
+        if (k_tail) zero_tail(kt, ks, af[cur]);
+        mfma_step(af[cur], bfr[cur]);
+      }
+      constexpr int last = (KSTEPS - 1) & 1;       // fragments of the last k step, still to multiply
+      if (k_tail) zero_tail(kt, KSTEPS - 1, af[last]);
+      if (kt + 1 < nk) {
+        publish(kt + 1);
+        const char* An = smem + ((kt + 1) % NSTAGE) * STAGE_BYTES;
+        load_frags(An, An + A_BYTES, 0, af[last ^ 1], bfr[last ^ 1]);
+      }
+      mfma_step(af[last], bfr[last]);
+    }
     }
 
+    if ((BTX_EXP & 128) && !(BTX_PINGPONG && NW == 8 && NSTAGE == 2) && lane == 0 && g.dg_part) {
+      float* o = g.dg_part + ((size_t)blockIdx.x * NW + wave) * 4;
+      o[0] = (float)dbg_wait; o[1] = (float)dbg_bar; o[2] = (float)(__builtin_readcyclecounter() - dbg_t0); o[3] = (float)nk;
+    }
     // ---- epilogue ----------------------------------------------------------
     // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
     //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
@@ -423,7 +561,8 @@ int launch(MArgs g, hipStream_t s) {
   constexpr int BNH = G::DUAL ? BN / 2 : BN;
   g.tiles_n = ceil_div(g.N, BNH);
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
-  const int total = g.tiles_m * g.tiles_n * (G::GROUP_K ? g.E : 1);
+  const int total = ceil_div(g.tiles_m, BTX_SUP_M) * ceil_div(g.tiles_n, BTX_SUP_N) * (BTX_SUP_M * BTX_SUP_N) *
+                    (G::GROUP_K ? g.E : 1);
   auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSTAGE, MODE>;
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
   if (!attr_set) {
