@@ -32,17 +32,13 @@
 #define BTX_SUP_N 16
 #define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
 #endif
-#ifndef BTX_SETPRIO
-#define BTX_SETPRIO 1
+#ifndef BTX_SUP_M
+#define BTX_SUP_M 16   // supertile: row tiles x column tiles that run concurrently chip-wide
+#define BTX_SUP_N 16
+#define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
 #endif
-#ifndef BTX_PINGPONG
-#define BTX_PINGPONG 1
-#endif
-#ifndef BTX_ISSUE_PARTS
-#define BTX_ISSUE_PARTS 1   // k steps over which the copies of the next tile are spread (1 = all at once)
-#endif
-#ifndef BTX_EXP
-#define BTX_EXP 0   // dev experiments only (bit 0: no global copies, bit 1: no LDS reads, bit 2: no MFMA)
+#ifndef BTX_TIMERS
+#define BTX_TIMERS 0   // dev only: per-phase cycle counters written to MArgs::dg_part
 #endif
 
 namespace btx {
@@ -98,7 +94,7 @@ __device__ __forceinline__ void copy16_to_lds(const void* base, uint32_t byte_of
                : "memory");
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
 struct Gemm {
   static constexpr bool A_KC = (MODE != DW13 && MODE != DW2);   // A's K index contiguous in memory
   static constexpr bool B_KC = (MODE == BWD_ACT || MODE == BWD_DX);
@@ -110,8 +106,15 @@ struct Gemm {
   static constexpr int TNH = DUAL ? TN / 2 : TN;
   static constexpr int BNH = DUAL ? BN / 2 : BN;               // output columns per B panel
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = STAGE_BYTES * NSTAGE;
+  // LDS: NSA stages of the A tile, then NSB stages of the B tile.  NSA == NSB: plain
+  // multi-stage pipeline.  NSA == 3, NSB == 2 (8 wavefronts, BK == 64): ping-pong schedule.
+  static constexpr int B_BASE = NSA * A_BYTES;
+  static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
+  static constexpr bool PINGPONG = (NSA == 3 && NSB == 2);
+  static constexpr int NSTAGE = NSB;
+  static_assert(PINGPONG || NSA == NSB, "stage counts");
+  static_assert(!PINGPONG || (WM * WN == 8 && BK == 64), "ping-pong needs 8 wavefronts and 4 k steps");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   static constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // per wavefront per tile
   static constexpr int KSTEPS = BK / 16;
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split into 1 KB wave copies");
@@ -120,10 +123,7 @@ struct Gemm {
 
   // ---- LDS addressing ----------------------------------------------------
   // K-contiguous tile: [rows][BK], 16-byte chunks XOR-swizzled by row
-  static __device__ __forceinline__ int kc_swz(int row) {
-    if (BTX_EXP & 16) return 0;
-    return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
-  }
+  static __device__ __forceinline__ int kc_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
   // strided-K tile: [BK][COLS], 16-byte chunk index XORed with (k & 3) << 2
 
   // byte offset inside a wave's copy `seg` (1 KB each) -> global element offset, for both layouts
@@ -140,7 +140,7 @@ struct Gemm {
       const int k = o / PITCH;
       const int phys = (o % PITCH) / 16;
       major = k;                                // k row of the tile
-      minor_elem = (phys ^ ((BTX_EXP & 32) ? 0 : ((k & 3) << 2))) * 8; // column offset inside the tile
+      minor_elem = (phys ^ ((k & 3) << 2)) * 8; // column offset inside the tile
     }
   }
 
@@ -251,33 +251,37 @@ struct Gemm {
     const int nk = MODE == BWD_DX ? 2 * nk1 : nk1;
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
 
-    // Copies of tile kt; part p of nparts issues every nparts-th copy, so that the copies can
-    // be spread between the MFMA groups of the tile being computed instead of stalling every
-    // wavefront at the top of the iteration while the address unit drains them.
-    auto issue = [&](int kt, int part, int nparts) {
-      if (BTX_EXP & 1) return;
-      const uint32_t stage = smem_base + (kt % NSTAGE) * STAGE_BYTES;
-      const bool pass2 = MODE == BWD_DX && kt >= nk1;
-      const int k0 = k_begin + (pass2 ? kt - nk1 : kt) * BK;
+    // Copies of the A / B part of tile kt into LDS stage kt % NSA / kt % NSB.
+    auto tile_k0 = [&](int kt, bool& pass2) {
+      pass2 = MODE == BWD_DX && kt >= nk1;
+      return k_begin + (pass2 ? kt - nk1 : kt) * BK;
+    };
+    auto issueA = [&](int kt) {
+      bool pass2;
+      const int k0 = tile_k0(kt, pass2);
+      const uint32_t stage = smem_base + (kt % NSA) * A_BYTES;
       const bf16_t* Ab = pass2 ? g.A1 : g.A0;
-      Ab += A_KC ? (size_t)((BTX_EXP & 8) ? 0 : row0) * g.lda + k0 : (size_t)k0 * g.lda;
-      const bf16_t* B0b = ((BTX_EXP & 8) ? g.B0 : Bp0) + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
+      Ab += A_KC ? (size_t)row0 * g.lda + k0 : (size_t)k0 * g.lda;
+#pragma unroll
+      for (int q = 0; q < A_LOADS; ++q) {
+        uint32_t off = a_off[q];
+        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
+        if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
+        copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
+      }
+    };
+    auto issueB = [&](int kt) {
+      bool pass2;
+      const int k0 = tile_k0(kt, pass2);
+      const uint32_t stage = smem_base + B_BASE + (kt % NSB) * B_BYTES;
+      const bf16_t* B0b = Bp0 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
       const bf16_t* B1b = Bp1 ? Bp1 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb) : nullptr;
 #pragma unroll
-      for (int q = 0; q < A_LOADS + B_LOADS; ++q) {
-        if (q % nparts != part) continue;
-        if (q < A_LOADS) {
-          uint32_t off = a_off[q];
-          // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
-          if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
-          copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
-        } else {
-          const int qb = q - A_LOADS;
-          uint32_t off = b_off[qb];
-          if (GROUP_K) off = (uint32_t)((min(k0 + b_k[qb], g.R - 1) - k0) * g.ldb + b_c[qb]) * 2u;
-          const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[qb]);
-          copy16_to_lds(second ? B1b : B0b, off, stage + A_BYTES + (wave * B_LOADS + qb) * 1024);
-        }
+      for (int q = 0; q < B_LOADS; ++q) {
+        uint32_t off = b_off[q];
+        if (GROUP_K) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
+        const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[q]);
+        copy16_to_lds(second ? B1b : B0b, off, stage + (wave * B_LOADS + q) * 1024);
       }
     };
 
@@ -289,55 +293,26 @@ struct Gemm {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    constexpr int PER_TILE = A_LOADS + B_LOADS;
-#pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-      if (s < nk) issue(s, 0, 1);
-
-    auto load_frags = [&](const char* At, const char* Bt, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+    auto load_frags = [&](int kt, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+      const char* At = smem + (kt % NSA) * A_BYTES;
+      const char* Bt = smem + B_BASE + (kt % NSB) * B_BYTES;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int r = wm * (TM * 32) + i * 32;
-        if (BTX_EXP & 2) { for (int x = 0; x < 8; ++x) af[i][x] = (__bf16)(float)(lane + i); continue; }
         af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int c = wn * (TNH * 32) + (j % TNH) * 32;
-        if (BTX_EXP & 2) { for (int x = 0; x < 8; ++x) bfr[j][x] = (__bf16)(float)(lane + j); continue; }
         bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
       }
-    };
-
-    unsigned long long dbg_wait = 0, dbg_bar = 0, dbg_t0 = 0;
-    if (BTX_EXP & 128) dbg_t0 = __builtin_readcyclecounter();
-
-    // Wait until tile kt has landed (up to NSTAGE-2 younger tiles may stay in flight) and
-    // publish it; passing the barrier also means every wavefront is done reading tile kt-1.
-    const bool tracing = (BTX_EXP & 256) && blockIdx.x == 300 && g.dg_part != nullptr;
-    auto trace = [&](int kt, int slot) {
-      if ((BTX_EXP & 256) && tracing && kt >= 60 && kt < 64 && lane == 0)
-        reinterpret_cast<unsigned long long*>(g.dg_part)[((kt - 60) * NW + wave) * 8 + slot] = __builtin_readcyclecounter();
-    };
-    auto publish = [&](int kt) {
-      unsigned long long c0 = 0, c1 = 0;
-      trace(kt - 1, 4);
-      if (BTX_EXP & 128) c0 = __builtin_readcyclecounter();
-      if (kt + NSTAGE - 2 < nk) wait_vmcnt((NSTAGE - 2) * PER_TILE);
-      else wait_vmcnt(0);
-      if (BTX_EXP & 128) c1 = __builtin_readcyclecounter();
-      trace(kt - 1, 5);
-      if (!(BTX_EXP & 64)) __syncthreads();
-      trace(kt, 0);
-      if (BTX_EXP & 128) { const unsigned long long c2 = __builtin_readcyclecounter(); dbg_wait += c1 - c0; dbg_bar += c2 - c1; }
     };
     auto mfma_step = [&](bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          if (BTX_EXP & 4) { acc[i][j][0] += (float)af[i][0] * (float)bfr[j][0]; }
-          else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     };
     // grouped-K: rows past the expert's last one belong to the next expert; zero A there
     auto zero_tail = [&](int kt, int ks, bf16x8 (&af)[TM]) {
@@ -349,53 +324,62 @@ struct Gemm {
           if (kb + x >= k_len) af[i][x] = (__bf16)0.0f;
     };
 
-    if (BTX_PINGPONG && NW == 8 && NSTAGE == 2 && KSTEPS % 2 == 0) {
+    if constexpr (PINGPONG) {
       // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) alternate
-      // between a memory phase (LDS fragment reads + the global->LDS copies of the next
-      // tile) and a compute phase (an uninterrupted run of MFMAs), half a period apart and
-      // kept in step by a barrier at every phase boundary.  The matrix pipe always has one
-      // wavefront feeding it and is never held up behind a wavefront that is stuck issuing
-      // copies or waiting for LDS.
+      // between a memory phase (LDS fragment reads of half a tile + a quarter of the copies
+      // of a later tile) and a compute phase (an uninterrupted run of 16 MFMAs), half a period
+      // apart and kept in step by a barrier at every phase boundary.  The matrix pipe always
+      // has one wavefront feeding it and is never held up behind a wavefront that is stuck
+      // issuing copies or waiting for LDS.  Time is counted in phases; tile kt occupies phases
+      // 4kt .. 4kt+3 for group 0 and one phase later for group 1:
+      //   phase 4kt   : G0 reads half 0 of tile kt, issues its B copies of tile kt+1   | G1 computes
+      //   phase 4kt+1 : G0 computes | G1 reads half 0 of tile kt, issues its B copies of tile kt+1
+      //   phase 4kt+2 : G0 reads half 1, issues its A copies of tile kt+2             | G1 computes
+      //   phase 4kt+3 : G0 computes | G1 reads half 1, issues its A copies of tile kt+2
+      // so the address unit sees the same 16 copies in every phase.  B has two LDS stages (its
+      // copies have at least 2.5 phases to land), A has three (at least 4 phases).  Every
+      // wavefront waits for its copies of tile kt+1 right before the barrier that ends phase
+      // 4kt+3; its 4 youngest copies (A of tile kt+2) may stay in flight.
       constexpr int HS = KSTEPS / 2;                 // k steps per half tile
-      const int grp = BTX_PINGPONG == 2 ? (wave & 1) : wave / (NW / 2);   // group 1 lags group 0 by one phase
+      const int grp = wave / (NW / 2);               // group 1 lags group 0 by one phase
       bf16x8 fa[HS][TM], fb[HS][TN];
+      unsigned long long tm = 0, tb1 = 0, tc = 0, tv = 0, tb2 = 0;
+      auto now = [&]() -> unsigned long long { return BTX_TIMERS ? __builtin_readcyclecounter() : 0ull; };
       if (nk > 0) {
-        wait_vmcnt(0);
+        issueA(0);
+        issueB(0);
+        if (nk > 1) issueA(1);
+        if (nk > 1) wait_vmcnt(A_LOADS); else wait_vmcnt(0);
         __builtin_amdgcn_s_barrier();                // tile 0 published
       }
-      if (grp == 1) __builtin_amdgcn_s_barrier();    // idle during group 0's first memory phase
-      unsigned long long tm = 0, tb1 = 0, tc = 0, tv = 0, tb2 = 0;   // BTX_EXP & 128: phase timers
-      auto now = [&]() -> unsigned long long { return (BTX_EXP & 128) ? __builtin_readcyclecounter() : 0ull; };
+      if (grp == 1 && nk > 0) __builtin_amdgcn_s_barrier();   // idle during group 0's first memory phase
       for (int kt = 0; kt < nk; ++kt) {
-        const char* At = smem + (kt % NSTAGE) * STAGE_BYTES;
-        const char* Bt = At + A_BYTES;
         const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           // ---- memory phase
           const unsigned long long t0 = now();
 #pragma unroll
-          for (int x = 0; x < HS; ++x) load_frags(At, Bt, h * HS + x, fa[x], fb[x]);
-          if (h == 0 && kt + 1 < nk) issue(kt + 1, 0, 1);
+          for (int x = 0; x < HS; ++x) load_frags(kt, h * HS + x, fa[x], fb[x]);
+          if (h == 0 && kt + 1 < nk) issueB(kt + 1);
+          if (h == 1 && kt + 2 < nk) issueA(kt + 2);
           if (k_tail) {
 #pragma unroll
             for (int x = 0; x < HS; ++x) zero_tail(kt, h * HS + x, fa[x]);
           }
           __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): fragments are in registers
           const unsigned long long t1 = now();
-          if (h == 1 && grp == 1) wait_vmcnt(0);     // group 1's copies of tile kt+1 have landed
+          if (h == 1 && grp == 1) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
           const unsigned long long t2 = now();
           __builtin_amdgcn_sched_barrier(0);
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
           const unsigned long long t3 = now();
           // ---- compute phase
-          if (BTX_SETPRIO) __builtin_amdgcn_s_setprio(BTX_SETPRIO);
 #pragma unroll
           for (int x = 0; x < HS; ++x) mfma_step(fa[x], fb[x]);
-          if (BTX_SETPRIO) __builtin_amdgcn_s_setprio(0);
           const unsigned long long t4 = now();
-          if (h == 1 && grp == 0) wait_vmcnt(0);     // group 0's copies of tile kt+1 have landed
+          if (h == 1 && grp == 0) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
           const unsigned long long t5 = now();
           __builtin_amdgcn_sched_barrier(0);
           if (!(grp == 1 && h == 1 && kt + 1 == nk)) __builtin_amdgcn_s_barrier();
@@ -404,49 +388,52 @@ struct Gemm {
           tm += t1 - t0; tv += (t2 - t1) + (t5 - t4); tb1 += t3 - t2; tc += t4 - t3; tb2 += t6 - t5;
         }
       }
-      if ((BTX_EXP & 128) && lane == 0 && g.dg_part) {
+      if (BTX_TIMERS && lane == 0 && g.dg_part) {
         float* o = g.dg_part + ((size_t)blockIdx.x * NW + wave) * 8;
         o[0] = (float)tm; o[1] = (float)tb1; o[2] = (float)tc; o[3] = (float)tb2; o[4] = (float)tv; o[5] = (float)nk;
       }
     } else {
-    // The loop is rotated by one k step: the MFMAs of a tile's last k step run after the
-    // barrier that publishes the next tile, right behind the LDS reads of that tile's first
-    // fragments, so the matrix pipe has work while those reads are in flight.
-    static_assert(KSTEPS % 2 == 0, "fragment double buffer assumes an even number of k steps");
-    bf16x8 af[2][TM], bfr[2][TN];
-    if (nk > 0) {
-      publish(0);
-      load_frags(smem, smem + A_BYTES, 0, af[0], bfr[0]);
-    }
-    for (int kt = 0; kt < nk; ++kt) {
-      const char* At = smem + (kt % NSTAGE) * STAGE_BYTES;
-      const char* Bt = At + A_BYTES;
-      const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
-      // the stage of tile kt+NSTAGE-1 was last read for tile kt-1: free since the last barrier
-      const bool prefetch = kt + NSTAGE - 1 < nk;
+      // Plain NSTAGE-deep pipeline, one barrier per tile.  The loop is rotated by one k step:
+      // the MFMAs of a tile's last k step run after the barrier that publishes the next tile,
+      // right behind the LDS reads of that tile's first fragments.
+      static_assert(KSTEPS % 2 == 0, "fragment double buffer assumes an even number of k steps");
+      constexpr int PER_TILE = A_LOADS + B_LOADS;
+      // wait until tile kt has landed (up to NSTAGE-2 younger tiles may stay in flight) and
+      // publish it; passing the barrier also means every wavefront is done reading tile kt-1
+      auto publish = [&](int kt) {
+        if (kt + NSTAGE - 2 < nk) wait_vmcnt((NSTAGE - 2) * PER_TILE);
+        else wait_vmcnt(0);
+        __syncthreads();
+      };
 #pragma unroll
-      for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
-        const int cur = ks & 1;
-        load_frags(At, Bt, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
-        if (prefetch) issue(kt + NSTAGE - 1, ks, BTX_ISSUE_PARTS);
-        if (k_tail) zero_tail(kt, ks, af[cur]);
-        mfma_step(af[cur], bfr[cur]);
+      for (int s = 0; s < NSTAGE - 1; ++s)
+        if (s < nk) { issueA(s); issueB(s); }
+      bf16x8 af[2][TM], bfr[2][TN];
+      if (nk > 0) {
+        publish(0);
+        load_frags(0, 0, af[0], bfr[0]);
       }
-      constexpr int last = (KSTEPS - 1) & 1;       // fragments of the last k step, still to multiply
-      if (k_tail) zero_tail(kt, KSTEPS - 1, af[last]);
-      if (kt + 1 < nk) {
-        publish(kt + 1);
-        const char* An = smem + ((kt + 1) % NSTAGE) * STAGE_BYTES;
-        load_frags(An, An + A_BYTES, 0, af[last ^ 1], bfr[last ^ 1]);
+      for (int kt = 0; kt < nk; ++kt) {
+        const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
+        // the stage of tile kt+NSTAGE-1 was last read for tile kt-1: free since the last barrier
+        if (kt + NSTAGE - 1 < nk) { issueA(kt + NSTAGE - 1); issueB(kt + NSTAGE - 1); }
+#pragma unroll
+        for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
+          const int cur = ks & 1;
+          load_frags(kt, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
+          if (k_tail) zero_tail(kt, ks, af[cur]);
+          mfma_step(af[cur], bfr[cur]);
+        }
+        constexpr int last = (KSTEPS - 1) & 1;       // fragments of the last k step, still to multiply
+        if (k_tail) zero_tail(kt, KSTEPS - 1, af[last]);
+        if (kt + 1 < nk) {
+          publish(kt + 1);
+          load_frags(kt + 1, 0, af[last ^ 1], bfr[last ^ 1]);
+        }
+        mfma_step(af[last], bfr[last]);
       }
-      mfma_step(af[last], bfr[last]);
-    }
     }
 
-    if ((BTX_EXP & 128) && !(BTX_PINGPONG && NW == 8 && NSTAGE == 2) && lane == 0 && g.dg_part) {
-      float* o = g.dg_part + ((size_t)blockIdx.x * NW + wave) * 4;
-      o[0] = (float)dbg_wait; o[1] = (float)dbg_bar; o[2] = (float)(__builtin_readcyclecounter() - dbg_t0); o[3] = (float)nk;
-    }
     // ---- epilogue ----------------------------------------------------------
     // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
     //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
@@ -454,12 +441,70 @@ struct Gemm {
     float dg_acc[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) dg_acc[i] = 0.f;
+
+    if constexpr (MODE == BWD_ACT) {
+      // The saved h1/h3 values of fragment row i+1 are requested before fragment row i is
+      // processed and stored, so their latency hides behind the arithmetic and the stores.
+      // Loads use clamped (always valid) addresses; only the stores are predicated.
+      u32x2 w1[2][TNH][4], w3[2][TNH][4];
+      float gate[2];
+      auto load_row = [&](int i, int b) {
+        const int m = min(row0 + wm * (TM * 32) + i * 32 + lane_m, row_end - 1);
+        gate[b] = g.gates[g.perm[m]];
+#pragma unroll
+        for (int j = 0; j < TNH; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = min(col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h, g.N - 4);
+            const size_t idx = (size_t)m * g.ldc + n;
+            w1[b][j][q] = *reinterpret_cast<const u32x2*>(g.H1 + idx);
+            w3[b][j][q] = *reinterpret_cast<const u32x2*>(g.H3 + idx);
+          }
+      };
+      load_row(0, 0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int b = i & 1;
+        if (i + 1 < TM) load_row(i + 1, b ^ 1);
+        const int m = row0 + wm * (TM * 32) + i * 32 + lane_m;
+        const bool m_ok = m < row_end;
+#pragma unroll
+        for (int j = 0; j < TNH; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h;
+            const u32x2 a1 = w1[b][j][q], a3 = w3[b][j][q];
+            const float z[4] = {bf16lo(a1[0]), bf16hi(a1[0]), bf16lo(a1[1]), bf16hi(a1[1])};
+            const float v3[4] = {bf16lo(a3[0]), bf16hi(a3[0]), bf16lo(a3[1]), bf16hi(a3[1])};
+            float o1[4], o3[4], oa[4], dot = 0.f;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              const float dd = acc[i][j][4 * q + x];
+              const float sg = sigmoid_f(z[x]), sl = z[x] * sg;
+              const float a = sl * v3[x];
+              dot = fmaf(dd, a, dot);
+              const float da = gate[b] * dd;
+              o1[x] = da * v3[x] * (sg * (1.f + z[x] * (1.f - sg)));
+              o3[x] = da * sl;
+              oa[x] = gate[b] * a;
+            }
+            if (m_ok && n < g.N) {
+              dg_acc[i] += dot;
+              const size_t idx = (size_t)m * g.ldc + n;
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
+                  u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
+                  u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
+                  u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
+            }
+          }
+      }
+    } else {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int m = row0 + wm * (TM * 32) + i * 32 + lane_m;
       const bool m_ok = m < row_end;
-      float gate = 0.f;
-      if (MODE == BWD_ACT && m_ok) gate = g.gates[g.perm[m]];
 #pragma unroll
       for (int j = 0; j < TNH; ++j) {
 #pragma unroll
@@ -483,29 +528,6 @@ struct Gemm {
             }
             *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
                 u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
-          } else if (MODE == BWD_ACT) {
-            const u32x2 w1 = *reinterpret_cast<const u32x2*>(g.H1 + idx);
-            const u32x2 w3 = *reinterpret_cast<const u32x2*>(g.H3 + idx);
-            const float z[4] = {bf16lo(w1[0]), bf16hi(w1[0]), bf16lo(w1[1]), bf16hi(w1[1])};
-            const float v3[4] = {bf16lo(w3[0]), bf16hi(w3[0]), bf16lo(w3[1]), bf16hi(w3[1])};
-            float o1[4], o3[4], oa[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-              const float dd = acc[i][j][4 * q + x];
-              const float sg = sigmoid_f(z[x]), sl = z[x] * sg;
-              const float a = sl * v3[x];
-              dg_acc[i] = fmaf(dd, a, dg_acc[i]);
-              const float da = gate * dd;
-              o1[x] = da * v3[x] * (sg * (1.f + z[x] * (1.f - sg)));
-              o3[x] = da * sl;
-              oa[x] = gate * a;
-            }
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
-                u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
-                u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
-                u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
           } else {
             // plain stores: DOWN, BWD_DX (bf16); DW13 / DW2 (bf16 or fp32, per-expert base)
             const size_t cidx = idx + (GROUP_K ? (size_t)e * g.strideC_e : 0);
@@ -524,6 +546,7 @@ struct Gemm {
           }
         }
       }
+    }
     }
     if (MODE == BWD_ACT) {
       // dg partial of this column tile: lanes l and l^32 hold the same row; then the WN
@@ -549,21 +572,21 @@ struct Gemm {
   }
 };
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
 __global__ __launch_bounds__(WM* WN* kWave) void mfma_gemm_kernel(MArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  Gemm<BM, BN, BK, WM, WN, NSTAGE, MODE>::run(g, smem);
+  Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE>::run(g, smem);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
 int launch(MArgs g, hipStream_t s) {
-  using G = Gemm<BM, BN, BK, WM, WN, NSTAGE, MODE>;
+  using G = Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
   constexpr int BNH = G::DUAL ? BN / 2 : BN;
   g.tiles_n = ceil_div(g.N, BNH);
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
   const int total = ceil_div(g.tiles_m, BTX_SUP_M) * ceil_div(g.tiles_n, BTX_SUP_N) * (BTX_SUP_M * BTX_SUP_N) *
                     (G::GROUP_K ? g.E : 1);
-  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSTAGE, MODE>;
+  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -592,7 +615,7 @@ int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
-  return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, UP>(g, s);
+  return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, UP>(g, s);
 }
 
 int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s) {
@@ -601,7 +624,7 @@ int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShape
   g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.d; g.ldc = sh.d;
   g.strideB_e = sh.s2; g.R = sh.R;
-  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, DOWN>(g, s);
+  return sh.f % 64 == 0 ? launch<256, 256, 64, 4, 2, 3, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, DOWN>(g, s);
 }
 
 int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
@@ -614,8 +637,8 @@ int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
   g.strideB_e = sh.s2; g.R = sh.R;
-  return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 2, BWD_ACT>(g, s)
-                        : launch<256, kActBN, 32, 2, 4, 4, BWD_ACT>(g, s);
+  return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT>(g, s)
+                        : launch<256, kActBN, 32, 2, 4, 4, 4, BWD_ACT>(g, s);
 }
 
 int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
@@ -625,7 +648,7 @@ int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3
   g.A0 = (const bf16_t*)dh1; g.A1 = (const bf16_t*)dh3; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = dxs;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.f; g.ldc = sh.d;
   g.strideB_e = sh.s13; g.R = sh.R;
-  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, BWD_DX>(g, s);
+  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, BWD_DX>(g, s);
 }
 
 int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
@@ -635,7 +658,7 @@ int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
   g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
-  return launch<256, 256, 64, 2, 4, 2, DW13>(g, s);
+  return launch<256, 256, 64, 2, 4, 2, 2, DW13>(g, s);
 }
 
 int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW2,
@@ -645,7 +668,7 @@ int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* o
   h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dys; h.C0 = dW2;
   h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = sh.d; h.ldc = sh.d;
   h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
-  return launch<256, 256, 64, 2, 4, 2, DW2>(h, s);
+  return launch<256, 256, 64, 2, 4, 2, 2, DW2>(h, s);
 }
 
 }  // namespace btx
