@@ -80,6 +80,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int t0 = blockIdx.x * kTokPerBlock + wave * kTokPerWave;
+  const bool vec4 = (E % EC) == 0 && (E % 4) == 0;
 
   // ---- logits -------------------------------------------------------------
   for (int e0 = 0; e0 < E; e0 += EC) {
@@ -99,8 +100,16 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
       for (int i = 0; i < 8; ++i) {
         float w[EC];
         const float* wp = Wr + (size_t)(c0 + i) * E + e0;
+        if (EC % 4 == 0 && vec4) {   // E % 4 == 0: whole 16-byte groups, all inside the row
 #pragma unroll
-        for (int j = 0; j < EC; ++j) w[j] = (e0 + j < E) ? wp[j] : 0.f;
+          for (int j = 0; j < EC; j += 4) {
+            const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + j);
+            w[j] = wv[0]; w[j + 1] = wv[1]; w[j + 2] = wv[2]; w[j + 3] = wv[3];
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < EC; ++j) w[j] = (e0 + j < E) ? wp[j] : 0.f;
+        }
 #pragma unroll
         for (int q = 0; q < kTokPerWave; ++q)
 #pragma unroll

@@ -145,37 +145,56 @@ __global__ __launch_bounds__(256) void dwr_reduce_kernel(const float* __restrict
   }
 }
 
-// One wavefront per token row.
+// One wavefront handles kDxTok token rows at a time so that every W_router element it loads
+// is used for all of them (W_router is [d,E] fp32: per 16 bytes of dX it costs 32*E bytes).
+constexpr int kDxTok = 4;
 template <typename XT>
 __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ dxs, const int32_t* __restrict__ inv_pos,
                                                         const float* __restrict__ ds, const float* __restrict__ Wr,
                                                         int T, int d, int E, int k, XT* __restrict__ dX) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int t = blockIdx.x * 4 + threadIdx.x / kWave;
-  if (t >= T) return;
-  const float my_ds = lane < E ? ds[(size_t)t * E + lane] : 0.f;
+  const int t0 = (blockIdx.x * 4 + threadIdx.x / kWave) * kDxTok;
+  if (t0 >= T) return;
+  float my_ds[kDxTok];
+#pragma unroll
+  for (int q = 0; q < kDxTok; ++q) my_ds[q] = (lane < E && t0 + q < T) ? ds[(size_t)(t0 + q) * E + lane] : 0.f;
   // The trip count is uniform so that every lane stays active for the cross-lane reads of ds.
   for (int base = 0; base < d; base += kWave * 8) {
     const int c0 = base + lane * 8;
     const bool in_row = c0 < d;
-    float acc[8] = {};
+    float acc[kDxTok][8] = {};
     if (in_row) {
-      for (int j = 0; j < k; ++j) {
-        const int r = inv_pos[(size_t)t * k + j];
-        float v[8];
-        Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+      for (int q = 0; q < kDxTok; ++q) {
+        if (t0 + q >= T) break;
+        for (int j = 0; j < k; ++j) {
+          const int r = inv_pos[(size_t)(t0 + q) * k + j];
+          float v[8];
+          Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[q][i] += v[i];
+        }
       }
     }
     for (int e = 0; e < E; ++e) {
-      const float w = __shfl(my_ds, e, kWave);
-      if (w != 0.f && in_row) {
+      float w[kDxTok];
+      bool any = false;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = fmaf(w, Wr[(size_t)(c0 + i) * E + e], acc[i]);
+      for (int q = 0; q < kDxTok; ++q) { w[q] = __shfl(my_ds[q], e, kWave); any = any || w[q] != 0.f; }
+      if (any && in_row) {   // `any` is uniform across the wave
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float wr = Wr[(size_t)(c0 + i) * E + e];
+#pragma unroll
+          for (int q = 0; q < kDxTok; ++q) acc[q][i] = fmaf(w[q], wr, acc[q][i]);
+        }
       }
     }
-    if (in_row) Ld8<XT>::st(dX + (size_t)t * d + c0, acc);
+    if (in_row) {
+#pragma unroll
+      for (int q = 0; q < kDxTok; ++q)
+        if (t0 + q < T) Ld8<XT>::st(dX + (size_t)(t0 + q) * d + c0, acc[q]);
+    }
   }
 }
 
@@ -212,11 +231,11 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
                                                                       a.dW_router, a.db_router);
   BTX_LAUNCH_CHECK();
   if (a.dtype == BTX_BF16)
-    dx_finish_kernel<bf16_t><<<ceil_div(a.T, 4), 256, 0, s>>>(static_cast<const bf16_t*>(a.dxs), a.inv_pos, ds,
+    dx_finish_kernel<bf16_t><<<ceil_div(a.T, 4 * kDxTok), 256, 0, s>>>(static_cast<const bf16_t*>(a.dxs), a.inv_pos, ds,
                                                              a.W_router, a.T, a.d, a.E, a.k,
                                                              static_cast<bf16_t*>(a.dX));
   else
-    dx_finish_kernel<float><<<ceil_div(a.T, 4), 256, 0, s>>>(static_cast<const float*>(a.dxs), a.inv_pos, ds,
+    dx_finish_kernel<float><<<ceil_div(a.T, 4 * kDxTok), 256, 0, s>>>(static_cast<const float*>(a.dxs), a.inv_pos, ds,
                                                             a.W_router, a.T, a.d, a.E, a.k, static_cast<float*>(a.dX));
   BTX_LAUNCH_CHECK();
   return BTX_OK;
