@@ -55,6 +55,27 @@ class HipEvents:
         return ms.value if rc == 0 else float("nan")
 
 
+def profiled_traffic(stage):
+    """HBM bytes per launch of the GEMM kernel of `stage`, from the committed rocprofv3 PMC
+    summary (FETCH_SIZE + WRITE_SIZE in KiB, scaled by the copy-kernel calibration stated
+    in that file); None when the summary is missing."""
+    path = os.path.join(ROOT, "profiles", "layer_fwd_bwd_c2_pmc_counters.txt")
+    if not os.path.exists(path):
+        return None
+    fetch = write = None
+    inside = False
+    for line in open(path):
+        if not line.startswith(" "):
+            inside = line.startswith("mfma_gemm_kernel<") and line.strip().endswith(" " + stage)
+        elif inside and "FETCH_SIZE" in line:
+            fetch = float(line.split()[1])
+        elif inside and "WRITE_SIZE" in line:
+            write = float(line.split()[1])
+    if fetch is None or write is None:
+        return None
+    return (fetch / 1.003 + write / 1.000) * 1024.0
+
+
 def cpu_baseline(L, W, sample_tokens):
     """The oracle, as it stands, on the first `sample_tokens` tokens of the batch."""
     from oracle import btx_oracle as O
@@ -152,7 +173,8 @@ def main():
                    "d_ff": f, "experts": E, "top_k": k},
         "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm[dominant]["tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+                     "traffic": profiled_traffic(dominant) if T == WORKLOAD["T"] else None,
+                     "algorithmic_flops": GEMM_STAGES[dominant] * d * f * R},
         "expert_gemms": {"ms": gemm_ms, "tflops": gemm_tflops, "frac_of_peak": gemm_tflops / PEAK_BF16_TFLOPS,
                          "layer_frac_of_peak": 18.0 * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                          "per_kernel": gemm},

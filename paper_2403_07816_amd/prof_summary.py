@@ -1,0 +1,51 @@
+"""Turn rocprofv3 CSV output (kernel stats, PMC counter collections) into the short text
+summaries kept under profiles/.
+
+  python -m paper_2403_07816_amd.prof_summary stats  <bench_kernel_stats.csv>
+  python -m paper_2403_07816_amd.prof_summary pmc    <pmc_counter_collection.csv> [...]
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import sys
+
+MODES = {0: "up_swiglu", 1: "down", 2: "bwd_act", 3: "bwd_dx", 4: "dw13", 5: "dw2"}
+
+
+def short(name: str) -> str:
+    name = name.replace("btx::(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+    if name.startswith("mfma_gemm_kernel<"):
+        args = name[len("mfma_gemm_kernel<"):-1].split(",")
+        name += " " + MODES.get(int(args[-1]), "?")
+    return name
+
+
+def stats(path: str) -> None:
+    rows = list(csv.DictReader(open(path)))
+    print(f"{'kernel':72s} {'calls':>5s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'pct':>7s}")
+    for r in rows:
+        if "btx::" not in r["Name"]:
+            continue
+        print(f"{short(r['Name'])[:72]:72s} {r['Calls']:>5s} {float(r['AverageNs']) / 1e3:10.1f} "
+              f"{float(r['MinNs']) / 1e3:10.1f} {float(r['MaxNs']) / 1e3:10.1f} {float(r['Percentage']):7.2f}")
+
+
+def pmc(paths) -> None:
+    agg = collections.OrderedDict()
+    for path in paths:
+        for r in csv.DictReader(open(path)):
+            if "btx" not in r["Kernel_Name"]:
+                continue
+            agg.setdefault(short(r["Kernel_Name"]), collections.OrderedDict()).setdefault(
+                r["Counter_Name"], []).append(float(r["Counter_Value"]))
+    for name, counters in agg.items():
+        print(name)
+        for c, v in counters.items():
+            print(f"    {c:34s} {sum(v) / len(v):18.0f}   (mean of {len(v)} dispatches)")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) < 3 or sys.argv[1] not in ("stats", "pmc"):
+        sys.exit(__doc__)
+    stats(sys.argv[2]) if sys.argv[1] == "stats" else pmc(sys.argv[2:])
