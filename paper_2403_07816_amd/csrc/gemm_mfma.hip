@@ -624,7 +624,7 @@ int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShape
   g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.d; g.ldc = sh.d;
   g.strideB_e = sh.s2; g.R = sh.R;
-  return sh.f % 64 == 0 ? launch<256, 256, 64, 4, 2, 3, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, DOWN>(g, s);
+  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, DOWN>(g, s);
 }
 
 int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
