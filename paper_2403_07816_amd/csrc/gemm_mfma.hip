@@ -28,12 +28,7 @@
 #include "gemm_generic.h"
 
 #ifndef BTX_SUP_M
-#define BTX_SUP_M 16   // supertile: row tiles x column tiles that run concurrently chip-wide
-#define BTX_SUP_N 16
-#define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
-#endif
-#ifndef BTX_SUP_M
-#define BTX_SUP_M 16   // supertile: row tiles x column tiles that run concurrently chip-wide
+#define BTX_SUP_M 16   // default supertile: row tiles x column tiles that run concurrently chip-wide
 #define BTX_SUP_N 16
 #define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
 #endif
@@ -59,6 +54,7 @@ struct MArgs {
   int R;                                // total grouped rows
   int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
   int c_is_f32;
+  int sup_m, sup_n, xcd_m;             // supertile shape in tiles, XCDs along its rows
 };
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -172,9 +168,8 @@ struct Gemm {
     // running at any moment share few operand panels chip-wide (little HBM / infinity-cache
     // traffic, short miss latency); inside it XCD x owns a (kSupM/kXcdM) x (kSupN/kXcdN)
     // sub-block, so that the panels its CUs stream meet in that XCD's L2.
-    constexpr int kSupM = BTX_SUP_M, kSupN = BTX_SUP_N, kXcdM = BTX_XCD_M, kXcdN = 8 / kXcdM;
-    constexpr int kSubM = kSupM / kXcdM, kSubN = kSupN / kXcdN;
-    static_assert(kSubM * kXcdM == kSupM && kSubN * kXcdN == kSupN, "supertile must split over 8 XCDs");
+    const int kSupM = g.sup_m, kSupN = g.sup_n, kXcdM = g.xcd_m, kXcdN = 8 / kXcdM;
+    const int kSubM = kSupM / kXcdM, kSubN = kSupN / kXcdN;
     const int sup_n = (g.tiles_n + kSupN - 1) / kSupN, sup_m = (g.tiles_m + kSupM - 1) / kSupM;
     int id = blockIdx.x;
     int e = 0;
@@ -584,7 +579,9 @@ int launch(MArgs g, hipStream_t s) {
   constexpr int BNH = G::DUAL ? BN / 2 : BN;
   g.tiles_n = ceil_div(g.N, BNH);
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
-  const int total = ceil_div(g.tiles_m, BTX_SUP_M) * ceil_div(g.tiles_n, BTX_SUP_N) * (BTX_SUP_M * BTX_SUP_N) *
+  if (g.sup_m == 0) { g.sup_m = BTX_SUP_M; g.sup_n = BTX_SUP_N; g.xcd_m = BTX_XCD_M; }
+  if (g.sup_m % g.xcd_m || 8 % g.xcd_m || g.sup_n % (8 / g.xcd_m) || (g.sup_m * g.sup_n) % 8) return BTX_ERR_INVALID_ARG;
+  const int total = ceil_div(g.tiles_m, g.sup_m) * ceil_div(g.tiles_n, g.sup_n) * (g.sup_m * g.sup_n) *
                     (G::GROUP_K ? g.E : 1);
   auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
@@ -615,6 +612,7 @@ int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
+  g.sup_m = 16; g.sup_n = 8; g.xcd_m = 4;     // 86 column tiles at f = 11008: 8-wide supertiles waste least
   return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, UP>(g, s);
 }
 
@@ -637,6 +635,7 @@ int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
   g.strideB_e = sh.s2; g.R = sh.R;
+  g.sup_m = 16; g.sup_n = 16; g.xcd_m = 8;
   return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT>(g, s)
                         : launch<256, kActBN, 32, 2, 4, 4, 4, BWD_ACT>(g, s);
 }
@@ -658,6 +657,7 @@ int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
   g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
+  g.sup_m = 16; g.sup_n = 8; g.xcd_m = 4;
   return launch<256, 256, 64, 2, 4, 2, 2, DW13>(g, s);
 }
 
@@ -668,6 +668,7 @@ int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* o
   h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dys; h.C0 = dW2;
   h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = sh.d; h.ldc = sh.d;
   h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
+  h.sup_m = 8; h.sup_n = 8; h.xcd_m = 4;
   return launch<256, 256, 64, 2, 4, 2, 2, DW2>(h, s);
 }
 
