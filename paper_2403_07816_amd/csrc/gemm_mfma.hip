@@ -32,6 +32,9 @@
 #define BTX_SUP_N 16
 #define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
 #endif
+#ifndef BTX_DEV
+#define BTX_DEV 0      // dev only: timing experiments
+#endif
 #ifndef BTX_TIMERS
 #define BTX_TIMERS 0   // dev only: per-phase cycle counters written to MArgs::dg_part
 #endif
@@ -55,6 +58,9 @@ struct MArgs {
   int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
   int c_is_f32;
   int sup_m, sup_n, xcd_m;             // supertile shape in tiles, XCDs along its rows
+#if BTX_DEV
+  int dev_flags, dev_delay;
+#endif
 };
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -88,6 +94,15 @@ __device__ __forceinline__ void copy16_to_lds(const void* base, uint32_t byte_of
                :
                : "s"(sl), "v"(byte_off), "s"(sp)
                : "memory");
+}
+
+// Epilogue staging band: 32 rows of ROWB bytes in LDS, 16-byte chunks XOR-swizzled by row so
+// that both the piece writes (PIECE bytes per lane, 32 rows at one column) and the
+// row-contiguous 16-byte reads are free of bank conflicts.
+template <int ROWB, int PIECE>
+__device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
+  constexpr int CPR = ROWB / 16, RP = ROWB >= 256 ? 1 : 256 / ROWB, STEP = PIECE / 8;
+  return (uint32_t)(r * ROWB + ((chunk ^ (((r / RP) * STEP) & (CPR - 1))) << 4));
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
@@ -184,6 +199,12 @@ struct Gemm {
     const int tile_n = (sup % sup_n) * kSupN + (xcd / kXcdM) * kSubN + slot / kSubM;
     if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
 
+#if BTX_DEV
+    if ((g.dev_flags & 2) && blockIdx.x < 256) {
+      const int slot8 = (g.dev_flags & 4) ? (blockIdx.x / 8) % 8 : blockIdx.x % 8;
+      for (int w = 0; w < slot8 * g.dev_delay; ++w) __builtin_amdgcn_s_sleep(127);
+    }
+#endif
     int row0, row_end, k_begin, k_end;
     if (GROUP_K) {
       row0 = tile_m * BM;
@@ -429,46 +450,68 @@ struct Gemm {
       }
     }
 
+#if BTX_DEV
+    if (g.dev_flags & 1) return;
+#endif
     // ---- epilogue ----------------------------------------------------------
     // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
     //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
+    // In that layout one store instruction would touch 32 rows with 16 bytes each.  Instead
+    // every wavefront turns its results around in a private piece of LDS, one band of 32 rows
+    // at a time: the lanes write their 4-column pieces, read the band back as 16-byte chunks
+    // that follow each other along a row, and store whole row segments (64 to 256 contiguous
+    // bytes per row).  BWD_ACT fetches the saved h1/h3 band the same way round.  The operand
+    // stages are dead by now: in the ping-pong schedule the barrier that ends group 0's last
+    // compute phase comes after group 1's last fragment read and after every copy has landed.
+    if (!PINGPONG) __syncthreads();
     const int lane_m = lane & 31, lane_h = lane >> 5;
+    const int wcol0 = col0 + wn * (TNH * 32);         // first output column of this wavefront (per panel)
     float dg_acc[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) dg_acc[i] = 0.f;
 
     if constexpr (MODE == BWD_ACT) {
-      // The saved h1/h3 values of fragment row i+1 are requested before fragment row i is
-      // processed and stored, so their latency hides behind the arithmetic and the stores.
-      // Loads use clamped (always valid) addresses; only the stores are predicated.
-      u32x2 w1[2][TNH][4], w3[2][TNH][4];
-      float gate[2];
-      auto load_row = [&](int i, int b) {
-        const int m = min(row0 + wm * (TM * 32) + i * 32 + lane_m, row_end - 1);
-        gate[b] = g.gates[g.perm[m]];
+      constexpr int ROWB = TNH * 64;                  // bytes per band row
+      constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
+      static_assert(3 * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
+      char* bufA = smem + wave * (3 * 32 * ROWB);
+      char* bufB = bufA + 32 * ROWB;
+      char* bufC = bufB + 32 * ROWB;
+      const int cr = lane / CPR, cc = lane % CPR;     // row (per pass) and chunk of the row-contiguous view
+      const int cn = wcol0 + cc * 8;
+      u32x4 p1[NI], p3[NI];
+      float gate_next;
+      // band i of h1/h3 in the row-contiguous view (clamped, always valid addresses)
+      auto fetch = [&](int i) {
+        const int mb = row0 + wm * (TM * 32) + i * 32;
 #pragma unroll
-        for (int j = 0; j < TNH; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int n = min(col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h, g.N - 4);
-            const size_t idx = (size_t)m * g.ldc + n;
-            w1[b][j][q] = *reinterpret_cast<const u32x2*>(g.H1 + idx);
-            w3[b][j][q] = *reinterpret_cast<const u32x2*>(g.H3 + idx);
-          }
+        for (int t = 0; t < NI; ++t) {
+          const size_t idx = (size_t)min(mb + t * RPI + cr, row_end - 1) * g.ldc + min(cn, g.N - 8);
+          p1[t] = *reinterpret_cast<const u32x4*>(g.H1 + idx);
+          p3[t] = *reinterpret_cast<const u32x4*>(g.H3 + idx);
+        }
+        gate_next = g.gates[g.perm[min(mb + lane_m, row_end - 1)]];
       };
-      load_row(0, 0);
+      fetch(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int b = i & 1;
-        if (i + 1 < TM) load_row(i + 1, b ^ 1);
-        const int m = row0 + wm * (TM * 32) + i * 32 + lane_m;
-        const bool m_ok = m < row_end;
+        const int mb = row0 + wm * (TM * 32) + i * 32;
+#pragma unroll
+        for (int t = 0; t < NI; ++t) {
+          const uint32_t o = stage_off<ROWB, 8>(t * RPI + cr, cc);
+          *reinterpret_cast<u32x4*>(bufA + o) = p1[t];
+          *reinterpret_cast<u32x4*>(bufB + o) = p3[t];
+        }
+        const float gate = gate_next;
+        if (i + 1 < TM) fetch(i + 1);                 // in flight during the arithmetic below
+        const bool m_ok = mb + lane_m < row_end;
 #pragma unroll
         for (int j = 0; j < TNH; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const int n = col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h;
-            const u32x2 a1 = w1[b][j][q], a3 = w3[b][j][q];
+            const uint32_t o = stage_off<ROWB, 8>(lane_m, 4 * j + q) + 8 * lane_h;
+            const u32x2 a1 = *reinterpret_cast<const u32x2*>(bufA + o);
+            const u32x2 a3 = *reinterpret_cast<const u32x2*>(bufB + o);
             const float z[4] = {bf16lo(a1[0]), bf16hi(a1[0]), bf16lo(a1[1]), bf16hi(a1[1])};
             const float v3[4] = {bf16lo(a3[0]), bf16hi(a3[0]), bf16lo(a3[1]), bf16hi(a3[1])};
             float o1[4], o3[4], oa[4], dot = 0.f;
@@ -478,70 +521,93 @@ struct Gemm {
               const float sg = sigmoid_f(z[x]), sl = z[x] * sg;
               const float a = sl * v3[x];
               dot = fmaf(dd, a, dot);
-              const float da = gate[b] * dd;
+              const float da = gate * dd;
               o1[x] = da * v3[x] * (sg * (1.f + z[x] * (1.f - sg)));
               o3[x] = da * sl;
-              oa[x] = gate[b] * a;
+              oa[x] = gate * a;
             }
-            if (m_ok && n < g.N) {
-              dg_acc[i] += dot;
-              const size_t idx = (size_t)m * g.ldc + n;
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
-                  u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
-                  u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
-                  u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
-            }
+            if (m_ok && wcol0 + j * 32 + 8 * q + 4 * lane_h < g.N) dg_acc[i] += dot;
+            // each lane overwrites exactly the pieces it has just read
+            *reinterpret_cast<u32x2*>(bufA + o) = u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
+            *reinterpret_cast<u32x2*>(bufB + o) = u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
+            *reinterpret_cast<u32x2*>(bufC + o) = u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
           }
-      }
-    } else {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = row0 + wm * (TM * 32) + i * 32 + lane_m;
-      const bool m_ok = m < row_end;
-#pragma unroll
-      for (int j = 0; j < TNH; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = col0 + wn * (TNH * 32) + j * 32 + 8 * q + 4 * lane_h;
-          if (!m_ok || n >= g.N) continue;
-          const size_t idx = (size_t)m * g.ldc + n;
-          if (MODE == UP) {
-            float h1[4], h3[4], a[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-              h1[x] = acc[i][j][4 * q + x];
-              h3[x] = acc[i][j + TNH][4 * q + x];
-              a[x] = silu_f(h1[x]) * h3[x];
-            }
-            if (g.C0) {
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C0) + idx) =
-                  u32x2{pack_bf16x2(h1[0], h1[1]), pack_bf16x2(h1[2], h1[3])};
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C1) + idx) =
-                  u32x2{pack_bf16x2(h3[0], h3[1]), pack_bf16x2(h3[2], h3[3])};
-            }
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(g.C2) + idx) =
-                u32x2{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3])};
-          } else {
-            // plain stores: DOWN, BWD_DX (bf16); DW13 / DW2 (bf16 or fp32, per-expert base)
-            const size_t cidx = idx + (GROUP_K ? (size_t)e * g.strideC_e : 0);
-#pragma unroll
-            for (int p = 0; p < (DUAL ? 2 : 1); ++p) {
-              const f32x16& t = acc[i][j + p * TNH];
-              void* C = p ? g.C1 : g.C0;
-              if (GROUP_K && g.c_is_f32) {
-                *reinterpret_cast<f32x4*>(static_cast<float*>(C) + cidx) =
-                    f32x4{t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
-              } else {
-                *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(C) + cidx) =
-                    u32x2{pack_bf16x2(t[4 * q], t[4 * q + 1]), pack_bf16x2(t[4 * q + 2], t[4 * q + 3])};
-              }
-            }
+        for (int t = 0; t < NI; ++t) {
+          const int r = t * RPI + cr;
+          const uint32_t o = stage_off<ROWB, 8>(r, cc);
+          const u32x4 v1 = *reinterpret_cast<const u32x4*>(bufA + o);
+          const u32x4 v3 = *reinterpret_cast<const u32x4*>(bufB + o);
+          const u32x4 va = *reinterpret_cast<const u32x4*>(bufC + o);
+          if (mb + r < row_end && cn < g.N) {
+            const size_t idx = (size_t)(mb + r) * g.ldc + cn;
+            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = v1;
+            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = v3;
+            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = va;
           }
         }
       }
-    }
+    } else {
+      constexpr int NP = MODE == UP ? 3 : (DUAL ? 2 : 1);            // matrices written
+      // ET: element type of the output (bf16 bits or float)
+      auto staged = [&](auto tag) {
+        using ET = decltype(tag);
+        constexpr int ES = sizeof(ET);
+        constexpr int ROWB = TNH * 32 * ES, PIECE = 4 * ES;
+        constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
+        static_assert(ROWB == 64 || ROWB == 128 || ROWB == 256, "band row");
+        static_assert(NP * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
+        char* wb = smem + wave * (NP * 32 * ROWB);
+        const int cr = lane / CPR, cc = lane % CPR;
+        const int cn = wcol0 + cc * (16 / ES);
+        const bool want_h = MODE != UP || g.C0 != nullptr;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int mb = row0 + wm * (TM * 32) + i * 32;
+#pragma unroll
+          for (int j = 0; j < TNH; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              // 4 columns starting at j*32 + 8q + 4*lane_h of this wavefront's row segment
+              const uint32_t o = ES == 2 ? stage_off<ROWB, PIECE>(lane_m, 4 * j + q) + 8 * lane_h
+                                         : stage_off<ROWB, PIECE>(lane_m, 8 * j + 2 * q + lane_h);
+              float v[NP][4];
+#pragma unroll
+              for (int x = 0; x < 4; ++x) {
+                if constexpr (MODE == UP) {
+                  v[0][x] = acc[i][j][4 * q + x];
+                  v[1][x] = acc[i][j + TNH][4 * q + x];
+                  v[2][x] = silu_f(v[0][x]) * v[1][x];
+                } else {
+#pragma unroll
+                  for (int pp = 0; pp < NP; ++pp) v[pp][x] = acc[i][j + pp * TNH][4 * q + x];
+                }
+              }
+#pragma unroll
+              for (int pp = 0; pp < NP; ++pp) {
+                if (MODE == UP && pp < 2 && !want_h) continue;
+                char* dst = wb + pp * (32 * ROWB) + o;
+                if constexpr (ES == 2)
+                  *reinterpret_cast<u32x2*>(dst) = u32x2{pack_bf16x2(v[pp][0], v[pp][1]), pack_bf16x2(v[pp][2], v[pp][3])};
+                else
+                  *reinterpret_cast<f32x4*>(dst) = f32x4{v[pp][0], v[pp][1], v[pp][2], v[pp][3]};
+              }
+            }
+#pragma unroll
+          for (int pp = 0; pp < NP; ++pp) {
+            if (MODE == UP && pp < 2 && !want_h) continue;
+            ET* C = static_cast<ET*>(pp == 0 ? g.C0 : (pp == 1 ? g.C1 : g.C2)) + (GROUP_K ? (size_t)e * g.strideC_e : 0);
+#pragma unroll
+            for (int t = 0; t < NI; ++t) {
+              const int r = t * RPI + cr;
+              const u32x4 val = *reinterpret_cast<const u32x4*>(wb + pp * (32 * ROWB) + stage_off<ROWB, PIECE>(r, cc));
+              if (mb + r < row_end && cn < g.N) *reinterpret_cast<u32x4*>(C + (size_t)(mb + r) * g.ldc + cn) = val;
+            }
+          }
+        }
+      };
+      if (GROUP_K && g.c_is_f32) staged(float{});
+      else staged(bf16_t{});
     }
     if (MODE == BWD_ACT) {
       // dg partial of this column tile: lanes l and l^32 hold the same row; then the WN
