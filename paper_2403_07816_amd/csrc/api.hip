@@ -33,12 +33,16 @@ FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype) {
   return w;
 }
 
-struct BwdWs { void *xs, *dys, *dh1, *dh3, *ga, *dxs, *scratch, *router; float* dg_part; size_t bytes; };
+struct BwdWs { void *xs, *dysT, *dys, *dh1, *dh3, *ga, *dxs, *scratch, *router; float* dg_part; size_t bytes; };
 BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   const size_t R = (size_t)T * k, es = esize(dtype);
   Carver c(ws);
   BwdWs w;
-  w.xs = c.take(R * d * es);
+  // the dW products take x and dY either as grouped rows or transposed and padded
+  const bool tr = ff_dw_transposed(dtype, d, f);
+  const size_t dw_op = tr ? (size_t)d * ff_dw_pitch((int)R, E) * es : R * d * es;
+  w.xs = c.take(dw_op);
+  w.dysT = tr ? c.take(dw_op) : nullptr;
   w.dys = c.take(R * d * es);
   w.dh1 = c.take(R * f * es);
   w.dh3 = c.take(R * f * es);
@@ -195,9 +199,16 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
                                               w.dh3, w.ga, w.dg_part, w.scratch, s));
   BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s));
   if (n_dw == 3) {
-    BTX_STAGE(BTX_STAGE_GATHER_X_BWD, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
+    const bool tr = ff_dw_transposed(dtype, d, f);
+    auto gather_dw_operands = [&]() -> int {
+      if (!tr) return launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s);
+      const int pitch = ff_dw_pitch(R, E);
+      if (int rc = launch_gather_rows_t(x, w.xs, perm, offsets, R, k, d, E, pitch, s)) return rc;
+      return launch_gather_rows_t(dY, w.dysT, perm, offsets, R, k, d, E, pitch, s);
+    };
+    BTX_STAGE(BTX_STAGE_GATHER_X_BWD, gather_dw_operands());
     BTX_STAGE(BTX_STAGE_DW13, launch_bwd_dw13(dtype, dW_dtype, w.xs, w.dh1, w.dh3, offsets, sh, dW1, dW3, s));
-    BTX_STAGE(BTX_STAGE_DW2, launch_bwd_dw2(dtype, dW_dtype, w.ga, w.dys, offsets, sh, dW2, s));
+    BTX_STAGE(BTX_STAGE_DW2, launch_bwd_dw2(dtype, dW_dtype, w.ga, tr ? w.dysT : w.dys, offsets, sh, dW2, s));
   }
   RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, topk_idx,
                    gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,

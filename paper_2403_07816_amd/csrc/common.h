@@ -97,6 +97,10 @@ int launch_route(const RouteArgs& a, hipStream_t s);
 
 // rows: dst[r] = src[perm[r] / k]  (k = 1 with perm = NULL copies nothing; perm required)
 int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, int k, int d, int dtype, hipStream_t s);
+// bf16 only: dst[c][P_e + i] = src[perm[o_e + i] / k][c], every expert's rows padded with zeros to a
+// multiple of 64 (P_e = padded rows of the experts before e); dst is [d][pitch]
+int launch_gather_rows_t(const void* src, void* dst, const int32_t* perm, const int32_t* offsets, int R, int k, int d,
+                         int E, int pitch, hipStream_t s);
 // out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]   (gates NULL => unit weights)
 int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d,
                    int dtype, hipStream_t s);
@@ -117,7 +121,11 @@ int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, c
 // dxs = dh1 W1^T + dh3 W3^T
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
                   const FfShapes& sh, void* dxs, hipStream_t s);
-// dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows
+// dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows.  When
+// ff_dw_transposed() holds, xs and dys are passed in the transposed, padded form that
+// launch_gather_rows_t writes with pitch ff_dw_pitch(); otherwise as grouped rows.
+bool ff_dw_transposed(int dtype, int d, int f);
+int ff_dw_pitch(int R, int E);
 int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* offsets,
                     const FfShapes& sh, void* dW1, void* dW3, hipStream_t s);
 int launch_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* offsets, const FfShapes& sh,

@@ -13,6 +13,9 @@ size_t ff_scratch_bytes(int dtype, int R, int f) {
 // The MFMA kernels need d and f to be multiples of 32; other bf16 shapes take the plain path.
 static bool mfma_shape(int d, int f) { return d % 32 == 0 && f % 32 == 0 && d >= 64 && f >= 64; }
 
+bool ff_dw_transposed(int dtype, int d, int f) { return dtype == BTX_BF16 && mfma_shape(d, f); }
+int ff_dw_pitch(int R, int E) { return mfma_dw_pitch(R, E); }
+
 int bwd_act_partials(int dtype, int f) { return dtype == BTX_BF16 ? mfma_bwd_act_partials(f) : 1; }
 
 int launch_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* offsets,

@@ -12,8 +12,10 @@ int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3
                  float* dg_part, hipStream_t s);
 int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
                 const FfShapes& sh, void* dxs, hipStream_t s);
-int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
+// xsT / dysT: [d][mfma_dw_pitch(R, E)], experts' rows padded with zeros to multiples of 64
+int mfma_dw_pitch(int R, int E);
+int mfma_bwd_dw13(int dW_dtype, const void* xsT, const void* dh1, const void* dh3, const int32_t* off,
                   const FfShapes& sh, void* dW1, void* dW3, hipStream_t s);
-int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW2,
+int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dysT, const int32_t* off, const FfShapes& sh, void* dW2,
                  hipStream_t s);
 }  // namespace btx

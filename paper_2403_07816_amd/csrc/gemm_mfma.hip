@@ -107,8 +107,11 @@ __device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
 
 template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
 struct Gemm {
-  static constexpr bool A_KC = (MODE != DW13 && MODE != DW2);   // A's K index contiguous in memory
-  static constexpr bool B_KC = (MODE == BWD_ACT || MODE == BWD_DX);
+  // K index contiguous in memory?  In the dW products K is the grouped-row index: the operand
+  // with d columns (x for dW1/dW3, dY for dW2) arrives transposed, [d][padded rows], every
+  // expert's rows starting at a multiple of 64 and zero-filled up to the next one.
+  static constexpr bool A_KC = (MODE != DW2);
+  static constexpr bool B_KC = (MODE == BWD_ACT || MODE == BWD_DX || MODE == DW2);
   static constexpr bool DUAL = (MODE == UP || MODE == DW13);
   static constexpr bool GROUP_K = (MODE == DW13 || MODE == DW2);
   static constexpr int NW = WM * WN, NT = NW * kWave;
@@ -206,11 +209,13 @@ struct Gemm {
     }
 #endif
     int row0, row_end, k_begin, k_end;
+    int kp_begin = 0;                                   // first padded row of expert e (transposed operand)
     if (GROUP_K) {
       row0 = tile_m * BM;
       row_end = g.M;
       k_begin = g.offsets[e];
       k_end = g.offsets[e + 1];
+      for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
     } else {
       if (!find_row_tile(g.offsets, g.E, BM, tile_m, e, row0, row_end)) return;
       k_begin = 0;
@@ -268,13 +273,13 @@ struct Gemm {
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
 
     // Copies of the A / B part of tile kt into LDS stage kt % NSA / kt % NSB.
-    auto tile_k0 = [&](int kt, bool& pass2) {
+    auto tile_k0 = [&](int kt, bool kc, bool& pass2) {
       pass2 = MODE == BWD_DX && kt >= nk1;
-      return k_begin + (pass2 ? kt - nk1 : kt) * BK;
+      return (GROUP_K && kc ? kp_begin : k_begin) + (pass2 ? kt - nk1 : kt) * BK;
     };
     auto issueA = [&](int kt) {
       bool pass2;
-      const int k0 = tile_k0(kt, pass2);
+      const int k0 = tile_k0(kt, A_KC, pass2);
       const uint32_t stage = smem_base + (kt % NSA) * A_BYTES;
       const bf16_t* Ab = pass2 ? g.A1 : g.A0;
       Ab += A_KC ? (size_t)row0 * g.lda + k0 : (size_t)k0 * g.lda;
@@ -288,14 +293,14 @@ struct Gemm {
     };
     auto issueB = [&](int kt) {
       bool pass2;
-      const int k0 = tile_k0(kt, pass2);
+      const int k0 = tile_k0(kt, B_KC, pass2);
       const uint32_t stage = smem_base + B_BASE + (kt % NSB) * B_BYTES;
       const bf16_t* B0b = Bp0 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb);
       const bf16_t* B1b = Bp1 ? Bp1 + (B_KC ? (size_t)col0 * g.ldb + k0 : (size_t)k0 * g.ldb) : nullptr;
 #pragma unroll
       for (int q = 0; q < B_LOADS; ++q) {
         uint32_t off = b_off[q];
-        if (GROUP_K) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
+        if (GROUP_K && !B_KC) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
         const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[q]);
         copy16_to_lds(second ? B1b : B0b, off, stage + (wave * B_LOADS + q) * 1024);
       }
@@ -330,15 +335,7 @@ struct Gemm {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     };
-    // grouped-K: rows past the expert's last one belong to the next expert; zero A there
-    auto zero_tail = [&](int kt, int ks, bf16x8 (&af)[TM]) {
-      const int kb = kt * BK + ks * 16 + 8 * (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int x = 0; x < 8; ++x)
-          if (kb + x >= k_len) af[i][x] = (__bf16)0.0f;
-    };
+    // grouped-K: the k rows past an expert's last one meet the zero fill of the transposed operand
 
     if constexpr (PINGPONG) {
       // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) alternate
@@ -370,7 +367,6 @@ struct Gemm {
       }
       if (grp == 1 && nk > 0) __builtin_amdgcn_s_barrier();   // idle during group 0's first memory phase
       for (int kt = 0; kt < nk; ++kt) {
-        const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           // ---- memory phase
@@ -379,10 +375,6 @@ struct Gemm {
           for (int x = 0; x < HS; ++x) load_frags(kt, h * HS + x, fa[x], fb[x]);
           if (h == 0 && kt + 1 < nk) issueB(kt + 1);
           if (h == 1 && kt + 2 < nk) issueA(kt + 2);
-          if (k_tail) {
-#pragma unroll
-            for (int x = 0; x < HS; ++x) zero_tail(kt, h * HS + x, fa[x]);
-          }
           __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): fragments are in registers
           const unsigned long long t1 = now();
           if (h == 1 && grp == 1) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
@@ -430,18 +422,15 @@ struct Gemm {
         load_frags(0, 0, af[0], bfr[0]);
       }
       for (int kt = 0; kt < nk; ++kt) {
-        const bool k_tail = GROUP_K && (kt + 1) * BK > k_len;
         // the stage of tile kt+NSTAGE-1 was last read for tile kt-1: free since the last barrier
         if (kt + NSTAGE - 1 < nk) { issueA(kt + NSTAGE - 1); issueB(kt + NSTAGE - 1); }
 #pragma unroll
         for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
           const int cur = ks & 1;
           load_frags(kt, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
-          if (k_tail) zero_tail(kt, ks, af[cur]);
           mfma_step(af[cur], bfr[cur]);
         }
         constexpr int last = (KSTEPS - 1) & 1;       // fragments of the last k step, still to multiply
-        if (k_tail) zero_tail(kt, KSTEPS - 1, af[last]);
         if (kt + 1 < nk) {
           publish(kt + 1);
           load_frags(kt + 1, 0, af[last ^ 1], bfr[last ^ 1]);
@@ -555,7 +544,7 @@ struct Gemm {
         constexpr int ES = sizeof(ET);
         constexpr int ROWB = TNH * 32 * ES, PIECE = 4 * ES;
         constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
-        static_assert(ROWB == 64 || ROWB == 128 || ROWB == 256, "band row");
+        static_assert(ROWB == 64 || ROWB == 128 || ROWB == 256 || ROWB == 512, "band row");
         static_assert(NP * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
         char* wb = smem + wave * (NP * 32 * ROWB);
         const int cr = lane / CPR, cc = lane % CPR;
@@ -716,26 +705,28 @@ int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3
   return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, BWD_DX>(g, s);
 }
 
-int mfma_bwd_dw13(int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* off,
+int mfma_dw_pitch(int R, int E) { return (int)align_up((size_t)R, 64) + 64 * E; }
+
+int mfma_bwd_dw13(int dW_dtype, const void* xsT, const void* dh1, const void* dh3, const int32_t* off,
                   const FfShapes& sh, void* dW1, void* dW3, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
-  g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
+  g.A0 = (const bf16_t*)xsT; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
+  g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = mfma_dw_pitch(sh.R, sh.E); g.ldb = sh.f; g.ldc = sh.f;
   g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
   g.sup_m = 16; g.sup_n = 8; g.xcd_m = 4;
-  return launch<256, 256, 64, 2, 4, 2, 2, DW13>(g, s);
+  return launch<256, 256, 64, 2, 4, 3, 2, DW13>(g, s);
 }
 
-int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dys, const int32_t* off, const FfShapes& sh, void* dW2,
+int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dysT, const int32_t* off, const FfShapes& sh, void* dW2,
                  hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs h{};
-  h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dys; h.C0 = dW2;
-  h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = sh.d; h.ldc = sh.d;
+  h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dysT; h.C0 = dW2;
+  h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = mfma_dw_pitch(sh.R, sh.E); h.ldc = sh.d;
   h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
   h.sup_m = 8; h.sup_n = 8; h.xcd_m = 4;
-  return launch<256, 256, 64, 2, 4, 2, 2, DW2>(h, s);
+  return launch<256, 256, 64, 4, 2, 3, 2, DW2>(h, s);
 }
 
 }  // namespace btx

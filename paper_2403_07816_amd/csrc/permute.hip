@@ -1,6 +1,10 @@
 // Row movement around the expert GEMMs (both HBM-bound streaming kernels):
 //   gather_rows  dst[r] = src[perm[r] / k]: token rows copied into expert-grouped order
 //                (forward: x -> xs; backward: dY -> dys).
+//   gather_rows_t  the same rows, transposed and padded for the weight-gradient products,
+//                whose contraction runs over grouped rows: dst[c][P_e + i] = src[perm[o_e + i] / k][c]
+//                for row i of expert e, with P_e = sum over e' < e of n_e' rounded up to 64 and
+//                zeros from P_e + n_e to P_(e+1).  64 rows x 128 columns are turned around in LDS.
 //   combine      out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]: the gate-weighted sum of the
 //                layer equation (Sec. 3.2), one wavefront per token row, slots summed in
 //                ascending j in fp32, one rounding.  No atomics: every output row has
@@ -23,6 +27,48 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const u32x4* __re
   const u32x4* s = src + (size_t)t * chunks_per_row;
   u32x4* o = dst + (size_t)r * chunks_per_row;
   for (int c = lane; c < chunks_per_row; c += kWave) o[c] = s[c];
+}
+
+constexpr int kTRows = 64, kTCols = 128;
+__global__ __launch_bounds__(kThreads) void gather_rows_t_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                                 const int32_t* __restrict__ perm,
+                                                                 const int32_t* __restrict__ offsets, int E, int k,
+                                                                 int d, int pitch) {
+  __shared__ uint32_t tile[kTRows][kTCols / 2 + 1];     // +1 dword: the column reads below hit distinct banks
+  const int pb = blockIdx.x * kTRows;                   // first padded row of this block
+  int e = 0, P = 0, base = 0, n = 0;
+  for (; e < E; ++e) {
+    base = offsets[e];
+    n = offsets[e + 1] - base;
+    const int np = (n + kTRows - 1) & ~(kTRows - 1);
+    if (pb < P + np) break;
+    P += np;
+  }
+  if (e == E) return;
+  const int i0 = pb - P, c0 = blockIdx.y * kTCols;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = threadIdx.x / 16 + 16 * it, chunk = threadIdx.x % 16;
+    u32x4 v{0u, 0u, 0u, 0u};
+    if (i0 + row < n && c0 + 8 * chunk < d)
+      v = *reinterpret_cast<const u32x4*>(src + (size_t)(perm[base + i0 + row] / k) * d + c0 + 8 * chunk);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) tile[row][4 * chunk + x] = v[x];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int col = threadIdx.x / 8 + 32 * it, tc = threadIdx.x % 8;
+    uint32_t h[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const uint32_t w = tile[8 * tc + x][col >> 1];
+      h[x] = (col & 1) ? (w >> 16) : (w & 0xffffu);
+    }
+    if (c0 + col < d)
+      *reinterpret_cast<u32x4*>(dst + (size_t)(c0 + col) * pitch + pb + 8 * tc) =
+          u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+  }
 }
 
 template <typename ET> struct Chunk;  // 16 bytes of elements <-> floats
@@ -84,6 +130,16 @@ int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, i
   const int chunks = d * esz / 16;
   gather_rows_kernel<<<ceil_div(R, kThreads / kWave), kThreads, 0, s>>>(
       static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), perm, R, k, chunks);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
+
+int launch_gather_rows_t(const void* src, void* dst, const int32_t* perm, const int32_t* offsets, int R, int k, int d,
+                         int E, int pitch, hipStream_t s) {
+  if (pitch % 8 != 0 || pitch < (int)align_up((size_t)R, kTRows) + kTRows * E) return BTX_ERR_INVALID_ARG;
+  const dim3 grid(ceil_div(R, kTRows) + E, ceil_div(d, kTCols));
+  gather_rows_t_kernel<<<grid, kThreads, 0, s>>>(static_cast<const bf16_t*>(src), static_cast<bf16_t*>(dst), perm,
+                                                 offsets, E, k, d, pitch);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }
