@@ -108,7 +108,10 @@ def test_empty_batch_is_a_noop():
 
 # ------------------------------------------------------------------ bf16 path
 @pytest.mark.parametrize("T,d,f,E,k", [(512, 256, 384, 4, 2), (333, 264, 200, 4, 2), (1500, 512, 1376, 8, 4),
-                                       (40, 64, 72, 4, 1)])
+                                       (40, 64, 72, 4, 1),
+                                       # MFMA path at its edges: fewer rows than one k tile, many (mostly tiny or
+                                       # empty) experts, d and f that are multiples of 32 but not of 64
+                                       (5, 64, 64, 4, 2), (700, 96, 160, 64, 8), (257, 320, 96, 3, 3)])
 def test_bf16_forward_backward(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True)
 
@@ -119,8 +122,9 @@ def test_bf16_unrelated_experts_meet_the_plain_bar_on_router_gradients():
     run_layer_and_check(1024, 256, 384, 4, 2, BF16, unit_rms=True, expert_spread=3.0)
 
 
-def test_bf16_fp32_weight_gradients():
-    run_layer_and_check(300, 128, 256, 4, 2, BF16, unit_rms=True, dW_dtype=F32)
+@pytest.mark.parametrize("T,d,f", [(300, 128, 256), (150, 96, 416)])
+def test_bf16_fp32_weight_gradients(T, d, f):
+    run_layer_and_check(T, d, f, 4, 2, BF16, unit_rms=True, dW_dtype=F32)
 
 
 def test_bf16_switch_imbalanced():
