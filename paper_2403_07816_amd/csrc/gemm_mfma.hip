@@ -58,6 +58,7 @@ struct MArgs {
   int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
   int c_is_f32;
   int sup_m, sup_n, xcd_m;             // supertile shape in tiles, XCDs along its rows
+  int blocks_per_e;                     // grouped-K: block ids per expert (a multiple of 8)
 #if BTX_DEV
   int dev_flags, dev_delay;
 #endif
@@ -182,25 +183,49 @@ struct Gemm {
 
     // ---- which tile ------------------------------------------------------
     // Workgroups are dealt round-robin to the 8 XCDs (block id mod 8) and start in id order.
-    // kSupM x kSupN consecutive ids form one supertile of the tile grid, so that the tiles
-    // running at any moment share few operand panels chip-wide (little HBM / infinity-cache
-    // traffic, short miss latency); inside it XCD x owns a (kSupM/kXcdM) x (kSupN/kXcdN)
-    // sub-block, so that the panels its CUs stream meet in that XCD's L2.
-    const int kSupM = g.sup_m, kSupN = g.sup_n, kXcdM = g.xcd_m, kXcdN = 8 / kXcdM;
-    const int kSubM = kSupM / kXcdM, kSubN = kSupN / kXcdN;
-    const int sup_n = (g.tiles_n + kSupN - 1) / kSupN, sup_m = (g.tiles_m + kSupM - 1) / kSupM;
+    // SM x SN consecutive ids form one supertile of the tile grid, so that the tiles running at
+    // any moment share few operand panels chip-wide (little HBM / infinity-cache traffic, short
+    // miss latency); inside it XCD x owns a (SM/XM) x (SN/XN) sub-block, so that the panels its
+    // CUs stream meet in that XCD's L2.  Only whole supertiles are laid out like this.  The
+    // tiles right of and below the last whole supertile form one list (right strip row by row,
+    // then the bottom strip column by column) that is cut into 8 equal runs, one per XCD: a
+    // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
+    // tiles of the row-grouped products depends on the routing and is counted here.
+    const int SM = g.sup_m, SN = g.sup_n, XM = g.xcd_m, XN = 8 / XM;
+    int n_rt = g.tiles_m;
+    if (!GROUP_K) {
+      n_rt = 0;
+      for (int x = 0; x < g.E; ++x) n_rt += (g.offsets[x + 1] - g.offsets[x] + BM - 1) / BM;
+    }
+    const int fr = n_rt / SM, fc = g.tiles_n / SN;     // whole supertile rows / columns
+    const int blocks_full = fr * fc * SM * SN;
     int id = blockIdx.x;
     int e = 0;
     if (GROUP_K) {
-      const int per_e = sup_m * sup_n * (kSupM * kSupN);
-      e = id / per_e;
-      id -= e * per_e;
+      e = id / g.blocks_per_e;
+      id -= e * g.blocks_per_e;
     }
-    const int sup = id / (kSupM * kSupN), r = id % (kSupM * kSupN);
-    const int xcd = r % 8, slot = r / 8;
-    const int tile_m = (sup / sup_n) * kSupM + (xcd % kXcdM) * kSubM + slot % kSubM;
-    const int tile_n = (sup % sup_n) * kSupN + (xcd / kXcdM) * kSubN + slot / kSubM;
-    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
+    int tile_m, tile_n;
+    if (id < blocks_full) {
+      const int sup = id / (SM * SN), r = id % (SM * SN);
+      const int xcd = r % 8, slot = r / 8, sub_m = SM / XM, sub_n = SN / XN;
+      tile_m = (sup / fc) * SM + (xcd % XM) * sub_m + slot % sub_m;
+      tile_n = (sup % fc) * SN + (xcd / XM) * sub_n + slot / sub_m;
+    } else {
+      const int idl = id - blocks_full;
+      const int w = g.tiles_n - fc * SN, h = n_rt - fr * SM;   // strip width / height
+      const int n_right = fr * SM * w, n_left = n_right + h * g.tiles_n;
+      const int run = (n_left + 7) / 8;
+      const int l = (idl % 8) * run + idl / 8;
+      if (idl / 8 >= run || l >= n_left) return;
+      if (l < n_right) {
+        tile_m = l / w;
+        tile_n = fc * SN + l % w;
+      } else {
+        tile_m = fr * SM + (l - n_right) % h;
+        tile_n = (l - n_right) / h;
+      }
+    }
 
 #if BTX_DEV
     if ((g.dev_flags & 2) && blockIdx.x < 256) {
@@ -636,8 +661,9 @@ int launch(MArgs g, hipStream_t s) {
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
   if (g.sup_m == 0) { g.sup_m = BTX_SUP_M; g.sup_n = BTX_SUP_N; g.xcd_m = BTX_XCD_M; }
   if (g.sup_m % g.xcd_m || 8 % g.xcd_m || g.sup_n % (8 / g.xcd_m) || (g.sup_m * g.sup_n) % 8) return BTX_ERR_INVALID_ARG;
-  const int total = ceil_div(g.tiles_m, g.sup_m) * ceil_div(g.tiles_n, g.sup_n) * (g.sup_m * g.sup_n) *
-                    (G::GROUP_K ? g.E : 1);
+  // every tile has exactly one block id below (number of tiles) + 8; see the tile mapping
+  g.blocks_per_e = (int)align_up((size_t)g.tiles_m * g.tiles_n, 8) + 8;
+  const int total = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
   auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
   if (!attr_set) {
