@@ -693,7 +693,6 @@ int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t
   g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
-  g.sup_m = 16; g.sup_n = 8; g.xcd_m = 4;     // 86 column tiles at f = 11008: 8-wide supertiles waste least
   return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, UP>(g, s);
 }
 
@@ -716,7 +715,6 @@ int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
   g.strideB_e = sh.s2; g.R = sh.R;
-  g.sup_m = 16; g.sup_n = 16; g.xcd_m = 8;
   return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT>(g, s)
                         : launch<256, kActBN, 32, 2, 4, 4, 4, BWD_ACT>(g, s);
 }
@@ -740,7 +738,6 @@ int mfma_bwd_dw13(int dW_dtype, const void* xsT, const void* dh1, const void* dh
   g.A0 = (const bf16_t*)xsT; g.B0 = (const bf16_t*)dh1; g.B1 = (const bf16_t*)dh3; g.C0 = dW1; g.C1 = dW3;
   g.offsets = off; g.E = sh.E; g.M = sh.d; g.N = sh.f; g.lda = mfma_dw_pitch(sh.R, sh.E); g.ldb = sh.f; g.ldc = sh.f;
   g.strideC_e = sh.s13; g.R = sh.R; g.c_is_f32 = dW_dtype == BTX_F32;
-  g.sup_m = 16; g.sup_n = 8; g.xcd_m = 4;
   return launch<256, 256, 64, 2, 4, 3, 2, DW13>(g, s);
 }
 
@@ -751,7 +748,6 @@ int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dysT, const int32_t* 
   h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dysT; h.C0 = dW2;
   h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = mfma_dw_pitch(sh.R, sh.E); h.ldc = sh.d;
   h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
-  h.sup_m = 8; h.sup_n = 8; h.xcd_m = 4;
   return launch<256, 256, 64, 4, 2, 3, 2, DW2>(h, s);
 }
 
