@@ -24,7 +24,8 @@ FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype) {
   const size_t R = (size_t)T * k, es = esize(dtype);
   Carver c(ws);
   FwdWs w;
-  w.xs = c.take(R * d * es);
+  // gathered token rows, unless the GEMMs read them through perm themselves
+  w.xs = ff_gather_fused(dtype, T, d, f) ? nullptr : c.take(R * d * es);
   w.act = c.take(R * f * es);
   w.y = c.take(R * d * es);
   w.h1 = c.take(R * f * es);  // used only when the caller does not keep h1/h3
@@ -43,7 +44,7 @@ BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   const size_t dw_op = tr ? (size_t)d * ff_dw_pitch((int)R, E) * es : R * d * es;
   w.xs = c.take(dw_op);
   w.dysT = tr ? c.take(dw_op) : nullptr;
-  w.dys = c.take(R * d * es);
+  w.dys = ff_gather_fused(dtype, T, d, f) ? nullptr : c.take(R * d * es);
   w.dh1 = c.take(R * f * es);
   w.dh3 = c.take(R * f * es);
   w.ga = c.take(R * f * es);
@@ -155,8 +156,10 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
   void* h1 = save_h1 ? save_h1 : w.h1;
   void* h3 = save_h3 ? save_h3 : w.h3;
-  BTX_STAGE(BTX_STAGE_GATHER_X, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
-  BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, w.xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
+  const bool fused = ff_gather_fused(dtype, T, d, f);
+  if (!fused) BTX_STAGE(BTX_STAGE_GATHER_X, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
+  const RowSource xs = fused ? RowSource{x, perm, k} : RowSource{w.xs, nullptr, 1};
+  BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
   BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, s));
   BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, out, T, k, d, dtype, s));
   return BTX_OK;
@@ -194,8 +197,10 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int R = T * k;
   const FfShapes sh{R, d, f, E, w13_expert_stride, w2_expert_stride};
-  BTX_STAGE(BTX_STAGE_GATHER_DY, launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s));
-  BTX_STAGE(BTX_STAGE_BWD_ACT, launch_bwd_act(dtype, w.dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1,
+  const bool fused = ff_gather_fused(dtype, T, d, f);
+  if (!fused) BTX_STAGE(BTX_STAGE_GATHER_DY, launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s));
+  const RowSource dys = fused ? RowSource{dY, perm, k} : RowSource{w.dys, nullptr, 1};
+  BTX_STAGE(BTX_STAGE_BWD_ACT, launch_bwd_act(dtype, dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1,
                                               w.dh3, w.ga, w.dg_part, w.scratch, s));
   BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s));
   if (n_dw == 3) {

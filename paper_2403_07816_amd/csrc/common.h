@@ -107,15 +107,20 @@ int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, vo
 
 // Expert GEMM stages.  `offsets` = E+1 grouped-row offsets on the device.
 struct FfShapes { int R, d, f, E; int64_t s13, s2; };
+// Grouped rows of a [.., d] operand: row r is row perm[r] / k of `base`, or simply row r of
+// `base` when perm is NULL (rows already gathered).  ff_gather_fused() says whether the
+// stages of a problem read token rows through perm themselves.
+struct RowSource { const void* base; const int32_t* perm; int k; };
+bool ff_gather_fused(int dtype, int T, int d, int f);
 // a = silu(xs W1) * (xs W3); h1/h3 stored when non-null
-int launch_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* offsets,
+int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* scratch, hipStream_t s);
 // y = act W2
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
                 hipStream_t s);
 // D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a
 int bwd_act_partials(int dtype, int f);
-int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                    float* dg_part, void* scratch, hipStream_t s);
 // dxs = dh1 W1^T + dh3 W3^T

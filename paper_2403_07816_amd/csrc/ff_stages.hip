@@ -16,25 +16,31 @@ static bool mfma_shape(int d, int f) { return d % 32 == 0 && f % 32 == 0 && d >=
 bool ff_dw_transposed(int dtype, int d, int f) { return dtype == BTX_BF16 && mfma_shape(d, f); }
 int ff_dw_pitch(int R, int E) { return mfma_dw_pitch(R, E); }
 
+bool ff_gather_fused(int dtype, int T, int d, int f) {
+  return dtype == BTX_BF16 && mfma_shape(d, f) && mfma_gather_ok(T, d);
+}
+
 int bwd_act_partials(int dtype, int f) { return dtype == BTX_BF16 ? mfma_bwd_act_partials(f) : 1; }
 
-int launch_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* offsets,
+int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* /*scratch*/, hipStream_t s) {
   if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_up_swiglu(xs, W1, W3, offsets, sh, h1, h3, act, s);
-  return generic_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, act, s);
+  if (xs.perm) return BTX_ERR_UNSUPPORTED;  // the plain path takes gathered rows
+  return generic_up_swiglu(dtype, xs.base, W1, W3, offsets, sh, h1, h3, act, s);
 }
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
                 hipStream_t s) {
   if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_down(act, W2, offsets, sh, y, s);
   return generic_down(dtype, act, W2, offsets, sh, y, s);
 }
-int launch_bwd_act(int dtype, const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                    float* dg_part, void* scratch, hipStream_t s) {
   if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) {
     return mfma_bwd_act(dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, s);
   }
-  return generic_bwd_act(dtype, dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, scratch, s);
+  if (dys.perm) return BTX_ERR_UNSUPPORTED;
+  return generic_bwd_act(dtype, dys.base, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, scratch, s);
 }
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
                   const FfShapes& sh, void* dxs, hipStream_t s) {

@@ -4,10 +4,12 @@
 
 namespace btx {
 int mfma_bwd_act_partials(int f);
-int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* h1,
-                   void* h3, void* act, hipStream_t s);
+// gathered A rows need every byte offset inside the source to fit 32 bits
+bool mfma_gather_ok(int T, int d);
+int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
+                   void* h1, void* h3, void* act, hipStream_t s);
 int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s);
-int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                  const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                  float* dg_part, hipStream_t s);
 int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,

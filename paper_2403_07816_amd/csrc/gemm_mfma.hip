@@ -50,6 +50,7 @@ struct MArgs {
   void* C0; void* C1; void* C2;         // UP: h1,h3,act; BWD_ACT: dh1,dh3,ga; DW13: dW1,dW3; else C0
   const bf16_t* H1; const bf16_t* H3;   // BWD_ACT inputs
   const float* gates; const int32_t* perm; float* dg_part; int n_part;
+  const int32_t* a_perm; int a_k;       // UP / BWD_ACT: A row r is row a_perm[r] / a_k of A0 (NULL: row r)
   const int32_t* offsets; int E;
   int M, N, K;                          // grouped-M: M unused; grouped-K: K unused
   int lda, ldb, ldc;                    // leading dimensions in elements
@@ -263,7 +264,10 @@ struct Gemm {
       int major, minor;
       copy_coords<A_KC, BM>(wave * A_LOADS + q, lane, major, minor);
       if (A_KC) {
-        a_off[q] = (uint32_t)((min(row0 + major, row_end - 1) - row0) * g.lda + minor) * 2u;
+        const int gr = min(row0 + major, row_end - 1);
+        // gathered rows: the offset is taken from the first row of A0 (it fits 32 bits, checked on the host)
+        a_off[q] = g.a_perm ? (uint32_t)(g.a_perm[gr] / g.a_k) * (uint32_t)(g.lda * 2) + (uint32_t)(minor * 2)
+                            : (uint32_t)((gr - row0) * g.lda + minor) * 2u;
         a_k[q] = a_c[q] = 0;
       } else {
         a_k[q] = major;
@@ -307,7 +311,7 @@ struct Gemm {
       const int k0 = tile_k0(kt, A_KC, pass2);
       const uint32_t stage = smem_base + (kt % NSA) * A_BYTES;
       const bf16_t* Ab = pass2 ? g.A1 : g.A0;
-      Ab += A_KC ? (size_t)row0 * g.lda + k0 : (size_t)k0 * g.lda;
+      Ab += A_KC ? (g.a_perm ? (size_t)0 : (size_t)row0 * g.lda) + k0 : (size_t)k0 * g.lda;
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
         uint32_t off = a_off[q];
@@ -686,11 +690,13 @@ bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh
 constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
 int mfma_bwd_act_partials(int f) { return ceil_div(f, kActBN); }
 
-int mfma_up_swiglu(const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh, void* h1,
-                   void* h3, void* act, hipStream_t s) {
+bool mfma_gather_ok(int T, int d) { return (int64_t)T * d * 2 < ((int64_t)1 << 32); }
+
+int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
+                   void* h1, void* h3, void* act, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)xs; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
+  g.A0 = (const bf16_t*)xs.base; g.a_perm = xs.perm; g.a_k = xs.k; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
   return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, UP>(g, s);
@@ -705,12 +711,13 @@ int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShape
   return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, DOWN>(g, s);
 }
 
-int mfma_bwd_act(const void* dys, const void* W2, const void* h1, const void* h3, const float* gates,
+int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                  const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                  float* dg_part, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)dys; g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = ga;
+  g.A0 = (const bf16_t*)dys.base; g.a_perm = dys.perm; g.a_k = dys.k;
+  g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = ga;
   g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3; g.gates = gates; g.perm = perm; g.dg_part = dg_part;
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
