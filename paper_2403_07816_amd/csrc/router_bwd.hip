@@ -6,7 +6,7 @@
 //                   <dY, expert output>), gate Jacobian, load-balancing term -> ds[T,E]
 //   dwr_partial     dW_router = x^T ds as per-token-chunk partial sums
 //   dwr_reduce      fixed-order sum of the partials (and of db_router)
-//   dx_finish       dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T
+//   dx_finish       dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T, W_router slice kept in registers
 #include "common.h"
 
 namespace btx {
@@ -108,13 +108,18 @@ __global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__
   const int c0 = (blockIdx.y * 256 + threadIdx.x) * kColsPerThread;
   if (c0 < d) {
     float acc[kColsPerThread][kEC] = {};
-    for (int q = 0; q < nt; ++q) {
-      float xv[8];
-      Ld8<XT>::ld(x + (size_t)(t0 + q) * d + c0, xv);
+    // 4 token rows in flight; rows past the chunk's end are read from a clamped address and
+    // meet the zeros of s_ds
+    for (int q = 0; q < nt; q += 4) {
+      float xv[4][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
+      for (int u = 0; u < 4; ++u) Ld8<XT>::ld(x + (size_t)min(t0 + q + u, T - 1) * d + c0, xv[u]);
 #pragma unroll
-        for (int j = 0; j < kEC; ++j) acc[i][j] = fmaf(xv[i], s_ds[q][j], acc[i][j]);
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int j = 0; j < kEC; ++j) acc[i][j] = fmaf(xv[u][i], s_ds[q + u][j], acc[i][j]);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -129,72 +134,91 @@ __global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__
   }
 }
 
+// 64 outputs per block; 4 thread groups each add every 4th partial, then the 4 sums are added
+// in group order (a fixed order, like everything else here).
 __global__ __launch_bounds__(256) void dwr_reduce_kernel(const float* __restrict__ part, const float* __restrict__ db_part,
                                                          int nchunk, int dE, int E, float* __restrict__ dWr,
                                                          float* __restrict__ db) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < dE) {
-    float a = 0.f;
-    for (int c = 0; c < nchunk; ++c) a += part[(size_t)c * dE + i];
-    dWr[i] = a;
-  }
+  __shared__ float s_sum[4][64];
+  const int o = threadIdx.x % 64, grp = threadIdx.x / 64;
+  const int i = blockIdx.x * 64 + o;
+  float a = 0.f;
+  if (i < dE)
+    for (int c = grp; c < nchunk; c += 4) a += part[(size_t)c * dE + i];
+  s_sum[grp][o] = a;
+  __syncthreads();
+  if (grp == 0 && i < dE) dWr[i] = (s_sum[0][o] + s_sum[1][o]) + (s_sum[2][o] + s_sum[3][o]);
   if (db && blockIdx.x == 0 && threadIdx.x < E) {
-    float a = 0.f;
-    for (int c = 0; c < nchunk; ++c) a += db_part[(size_t)c * E + threadIdx.x];
-    db[threadIdx.x] = a;
+    float b = 0.f;
+    for (int c = 0; c < nchunk; ++c) b += db_part[(size_t)c * E + threadIdx.x];
+    db[threadIdx.x] = b;
   }
 }
 
-// One wavefront handles kDxTok token rows at a time so that every W_router element it loads
-// is used for all of them (W_router is [d,E] fp32: per 16 bytes of dX it costs 32*E bytes).
-constexpr int kDxTok = 4;
-template <typename XT>
+// dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T.  A wavefront owns 512 columns (8 per lane)
+// for kDxTok tokens, 4 of them in flight at a time; its slice of W_router ([d,E] fp32) stays in
+// registers when E <= EC, so the kernel streams dxs and dX and little else.
+constexpr int kDxTok = 16;
+template <typename XT, int EC>
 __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ dxs, const int32_t* __restrict__ inv_pos,
                                                         const float* __restrict__ ds, const float* __restrict__ Wr,
                                                         int T, int d, int E, int k, XT* __restrict__ dX) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int t0 = (blockIdx.x * 4 + threadIdx.x / kWave) * kDxTok;
-  if (t0 >= T) return;
-  float my_ds[kDxTok];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int c0 = ((blockIdx.y * 4 + wave) * kWave + lane) * 8;
+  const int t0 = blockIdx.x * kDxTok;
+  if (c0 >= d) return;                      // no cross-lane traffic below
+  const int n_ch = (E + EC - 1) / EC;
+  float wr[8][EC];
+  auto load_wr = [&](int e0) {
 #pragma unroll
-  for (int q = 0; q < kDxTok; ++q) my_ds[q] = (lane < E && t0 + q < T) ? ds[(size_t)(t0 + q) * E + lane] : 0.f;
-  // The trip count is uniform so that every lane stays active for the cross-lane reads of ds.
-  for (int base = 0; base < d; base += kWave * 8) {
-    const int c0 = base + lane * 8;
-    const bool in_row = c0 < d;
-    float acc[kDxTok][8] = {};
-    if (in_row) {
+    for (int i = 0; i < 8; ++i) {
+      const float* row = Wr + (size_t)(c0 + i) * E + e0;
+      if (E % 4 == 0) {                     // whole 16-byte groups, aligned
 #pragma unroll
-      for (int q = 0; q < kDxTok; ++q) {
-        if (t0 + q >= T) break;
-        for (int j = 0; j < k; ++j) {
-          const int r = inv_pos[(size_t)(t0 + q) * k + j];
-          float v[8];
-          Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
+        for (int v = 0; v < EC / 4; ++v) {
+          f32x4 w4{0.f, 0.f, 0.f, 0.f};
+          if (e0 + 4 * v < E) w4 = *reinterpret_cast<const f32x4*>(row + 4 * v);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc[q][i] += v[i];
+          for (int j = 0; j < 4; ++j) wr[i][4 * v + j] = w4[j];
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < EC; ++j) wr[i][j] = e0 + j < E ? row[j] : 0.f;
+      }
+    }
+  };
+  if (n_ch == 1) load_wr(0);
+  for (int tq = 0; tq < kDxTok; tq += 4) {
+    float acc[4][8] = {};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int t = t0 + tq + q;
+      if (t >= T) break;
+      for (int j = 0; j < k; ++j) {
+        float v[8];
+        Ld8<XT>::ld(dxs + (size_t)inv_pos[(size_t)t * k + j] * d + c0, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[q][i] += v[i];
+      }
+    }
+    for (int ch = 0; ch < n_ch; ++ch) {
+      if (n_ch > 1) load_wr(ch * EC);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int t = t0 + tq + q;
+        if (t >= T) break;
+#pragma unroll
+        for (int j = 0; j < EC; ++j) {
+          const int e = ch * EC + j;
+          const float w = e < E ? ds[(size_t)t * E + e] : 0.f;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[q][i] = fmaf(w, wr[i][j], acc[q][i]);
         }
       }
     }
-    for (int e = 0; e < E; ++e) {
-      float w[kDxTok];
-      bool any = false;
 #pragma unroll
-      for (int q = 0; q < kDxTok; ++q) { w[q] = __shfl(my_ds[q], e, kWave); any = any || w[q] != 0.f; }
-      if (any && in_row) {   // `any` is uniform across the wave
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float wr = Wr[(size_t)(c0 + i) * E + e];
-#pragma unroll
-          for (int q = 0; q < kDxTok; ++q) acc[q][i] = fmaf(w[q], wr, acc[q][i]);
-        }
-      }
-    }
-    if (in_row) {
-#pragma unroll
-      for (int q = 0; q < kDxTok; ++q)
-        if (t0 + q < T) Ld8<XT>::st(dX + (size_t)(t0 + q) * d + c0, acc[q]);
-    }
+    for (int q = 0; q < 4; ++q)
+      if (t0 + tq + q < T) Ld8<XT>::st(dX + (size_t)(t0 + tq + q) * d + c0, acc[q]);
   }
 }
 
@@ -227,16 +251,21 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
   else
     dwr_partial_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(a.x), ds, a.T, a.d, a.E, part, dbp);
   BTX_LAUNCH_CHECK();
-  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 256), 256, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E, a.E,
-                                                                      a.dW_router, a.db_router);
+  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 64), 256, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E, a.E,
+                                                                     a.dW_router, a.db_router);
   BTX_LAUNCH_CHECK();
-  if (a.dtype == BTX_BF16)
-    dx_finish_kernel<bf16_t><<<ceil_div(a.T, 4 * kDxTok), 256, 0, s>>>(static_cast<const bf16_t*>(a.dxs), a.inv_pos, ds,
-                                                             a.W_router, a.T, a.d, a.E, a.k,
-                                                             static_cast<bf16_t*>(a.dX));
-  else
-    dx_finish_kernel<float><<<ceil_div(a.T, 4 * kDxTok), 256, 0, s>>>(static_cast<const float*>(a.dxs), a.inv_pos, ds,
-                                                            a.W_router, a.T, a.d, a.E, a.k, static_cast<float*>(a.dX));
+  const dim3 dx_grid(ceil_div(a.T, kDxTok), ceil_div(a.d, 4 * kWave * 8));
+  auto dx_launch = [&](auto tag) {
+    using XT = decltype(tag);
+    const XT* dxs = static_cast<const XT*>(a.dxs);
+    XT* dX = static_cast<XT*>(a.dX);
+    if (a.E <= 4)
+      dx_finish_kernel<XT, 4><<<dx_grid, 256, 0, s>>>(dxs, a.inv_pos, ds, a.W_router, a.T, a.d, a.E, a.k, dX);
+    else
+      dx_finish_kernel<XT, 8><<<dx_grid, 256, 0, s>>>(dxs, a.inv_pos, ds, a.W_router, a.T, a.d, a.E, a.k, dX);
+  };
+  if (a.dtype == BTX_BF16) dx_launch(bf16_t{});
+  else dx_launch(float{});
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }
