@@ -30,6 +30,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
 WORKLOAD = dict(name="llama2-7b-shaped MoE-FF layer, fwd+bwd, T=16384 (4 seq x 4096), d=4096, f=11008, E=4, top-2, "
                      "bf16, load-balancing loss alpha=0.01",
                 T=16384, d=4096, f=11008, E=4, k=2, alpha=0.01)
+# FETCH_SIZE / WRITE_SIZE read this fraction of the known traffic of a plain streaming kernel (combine_kernel;
+# see profiles/layer_fwd_bwd_c2_pmc_counters.txt): 128-byte reads are counted as 64 bytes on this chip
+FETCH_FACTOR, WRITE_FACTOR = 0.5027, 1.000
 GEMM_STAGES = {"up_swiglu": 4, "down": 2, "bwd_act": 2, "bwd_dx": 4, "dw13": 4, "dw2": 2}   # x d*f*R flops
 
 
@@ -52,7 +55,10 @@ class HipEvents:
     def elapsed_ms(self, a, b):
         ms = ctypes.c_float()
         rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), ctypes.c_void_p(self.ev[a]), ctypes.c_void_p(self.ev[b]))
-        return ms.value if rc == 0 else 0.0   # a stage that launched nothing never records its events
+        if rc != 0:                          # a stage that launched nothing never records its events
+            self.hip.hipGetLastError()       # do not leave the failed query behind as a sticky error
+            return 0.0
+        return ms.value
 
 
 def profiled_traffic(stage):
@@ -73,7 +79,24 @@ def profiled_traffic(stage):
             write = float(line.split()[1])
     if fetch is None or write is None:
         return None
-    return (fetch / 1.003 + write / 1.000) * 1024.0
+    return (fetch / FETCH_FACTOR + write / WRITE_FACTOR) * 1024.0
+
+
+def sustained_mfma_tflops(data, ms_target=40.0):
+    """Register-fed bf16 MFMA rate on `data` (TFLOP/s): what the matrix cores sustain on this
+    chip, at the clock it settles to under that load, with operands like the layer's."""
+    B.btx_probe_mfma(data, 256, 2000)                      # warm-up, also settles the clock
+    torch.cuda.synchronize()
+    iters = 4000
+    for _ in range(2):                                     # second pass: ~ms_target long
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = B.btx_probe_mfma(data, 256, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        iters = max(1000, int(iters * ms_target / ms))
+    return flops / (ms * 1e-3) / 1e12
 
 
 def cpu_baseline(L, W, sample_tokens):
@@ -164,6 +187,7 @@ def main():
     gemm_tflops = 18.0 * d * f * R / (gemm_ms * 1e-3) / 1e12
 
     ms_per_step = elapsed / args.steps * 1e3
+    sustained = sustained_mfma_tflops(L["x"])
     result = {
         "metric": "MoE-FF layer tokens/s fwd+bwd (d4096,f11008,E4,top2)",
         "value": T * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -174,8 +198,11 @@ def main():
         "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm[dominant]["tflops"] / PEAK_BF16_TFLOPS,
                      "traffic": profiled_traffic(dominant) if T == WORKLOAD["T"] else None,
-                     "algorithmic_flops": GEMM_STAGES[dominant] * d * f * R},
+                     "algorithmic_flops": GEMM_STAGES[dominant] * d * f * R,
+                     # register-fed MFMA loop on the same x: the ceiling at the clock the chip sustains
+                     "sustained_mfma_peak": sustained, "frac_of_sustained": gemm[dominant]["tflops"] / sustained},
         "expert_gemms": {"ms": gemm_ms, "tflops": gemm_tflops, "frac_of_peak": gemm_tflops / PEAK_BF16_TFLOPS,
+                         "frac_of_sustained": gemm_tflops / sustained,
                          "layer_frac_of_peak": 18.0 * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                          "per_kernel": gemm},
         "stage_ms": stage_ms,

@@ -95,6 +95,18 @@ enum {
 };
 int btx_profile_stages(void** events, int n_pairs);
 
+/* Measurement aid, not part of the method: the rate the matrix cores sustain when fed from
+ * registers only.  n_blocks workgroups of 8 wavefronts each run `iters` rounds of 64
+ * v_mfma_f32_32x32x16_bf16 whose operands (16 fragments per lane, all pairs) are read once
+ * from `data` (DEVICE, 16-byte aligned, data_bytes >= 16, any bf16 values: use the kind of
+ * data the layer sees, the chip's clock under load depends on it).  out: DEVICE,
+ * btx_probe_mfma_out_bytes(n_blocks) bytes, overwritten with meaningless sums.  *flops (HOST,
+ * may be NULL) receives the floating-point operations of the launch; time the launch on
+ * `stream` yourself.  Errors: BTX_ERR_INVALID_ARG, BTX_ERR_HIP. */
+size_t btx_probe_mfma_out_bytes(int n_blocks);
+int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks, int iters, double* flops,
+                   void* stream);
+
 /* ---------------------------------------------------------------------------
  * btx_moe_route - router linear, softmax, selection, gates, load-balancing
  * statistics and the token -> expert grouping (Sec. 3.2: W_l x and

@@ -33,16 +33,30 @@ def stats(path: str) -> None:
 
 def pmc(paths) -> None:
     agg = collections.OrderedDict()
+    dur = collections.OrderedDict()     # kernel -> counter -> durations (ns) of the dispatches it was read on
     for path in paths:
         for r in csv.DictReader(open(path)):
             if "btx" not in r["Kernel_Name"]:
                 continue
-            agg.setdefault(short(r["Kernel_Name"]), collections.OrderedDict()).setdefault(
-                r["Counter_Name"], []).append(float(r["Counter_Value"]))
+            k = short(r["Kernel_Name"])
+            agg.setdefault(k, collections.OrderedDict()).setdefault(r["Counter_Name"], []).append(
+                float(r["Counter_Value"]))
+            dur.setdefault(k, {}).setdefault(r["Counter_Name"], []).append(
+                float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
     for name, counters in agg.items():
         print(name)
         for c, v in counters.items():
             print(f"    {c:34s} {sum(v) / len(v):18.0f}   (mean of {len(v)} dispatches)")
+        mean = {c: sum(v) / len(v) for c, v in counters.items()}
+        if "GRBM_GUI_ACTIVE" in mean:
+            # GRBM_GUI_ACTIVE is summed over the 8 XCDs, SQ_VALU_MFMA_BUSY_CYCLES over the 1024 SIMDs
+            cyc = mean["GRBM_GUI_ACTIVE"] / 8.0
+            d = dur[name]["GRBM_GUI_ACTIVE"]
+            ns = sum(d) / len(d)
+            line = f"    derived: {ns / 1e3:9.1f} us per dispatch in this run, {cyc / ns:5.2f} GHz mean clock"
+            if mean.get("SQ_VALU_MFMA_BUSY_CYCLES", 0) > 0:
+                line += f", MFMA busy {mean['SQ_VALU_MFMA_BUSY_CYCLES'] / 1024.0 / cyc * 100:4.1f} % of active cycles"
+            print(line)
 
 
 if __name__ == "__main__":

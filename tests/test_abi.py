@@ -101,6 +101,17 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert lib.btx_merge_average(arr, 2, p, -1, 0, null) == 1
 
 
+def test_probe_rejects_bad_arguments(lib):
+    bad = 1  # BTX_ERR_INVALID_ARG
+    dummy = ctypes.c_void_p(0x1000)
+    assert lib.btx_probe_mfma(None, 1024, dummy, 256, 10, None, None) == bad
+    assert lib.btx_probe_mfma(dummy, 8, dummy, 256, 10, None, None) == bad          # less than one 16-byte chunk
+    assert lib.btx_probe_mfma(ctypes.c_void_p(0x1008), 1024, dummy, 256, 10, None, None) == bad   # misaligned
+    assert lib.btx_probe_mfma(dummy, 1024, dummy, 0, 10, None, None) == bad
+    assert lib.btx_probe_mfma(dummy, 1024, dummy, 256, 0, None, None) == bad
+    assert lib.btx_probe_mfma_out_bytes(256) == 256 * 512 * 4
+
+
 def test_missing_library_raises(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libbtx_moe.so")

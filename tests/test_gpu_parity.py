@@ -168,3 +168,11 @@ def test_merge_in_place():
     want = B.btx_merge_average(sets)
     B.btx_merge_average(sets, out=sets[0])
     assert torch.equal(sets[0], want)
+
+
+# ------------------------------------------------------------ measurement aid
+def test_mfma_probe_runs_and_counts_its_flops():
+    data = torch.randn(1 << 20, device="cuda").to(torch.bfloat16)
+    flops = B.btx_probe_mfma(data, n_blocks=8, iters=3)
+    torch.cuda.synchronize()
+    assert flops == 2.0 * 32 * 32 * 16 * 64 * 3 * 8 * 8
