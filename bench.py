@@ -99,6 +99,18 @@ def sustained_mfma_tflops(data, ms_target=40.0):
     return flops / (ms * 1e-3) / 1e12
 
 
+def hbm_stages(stage_ms, T, d, E, k, s=2):
+    """The streaming stages against the 8 TB/s HBM peak: algorithmic bytes per token (bf16 rows of d*s bytes) and
+    the rate they were moved at.  route: x read once + indices, gates, probabilities written; combine: k rows read,
+    one written; gather_x_bwd: x and dY each read once per routed slot and written once per slot, transposed;
+    router_bwd: x read (dW_router), k rows of dxs read and one row of dX written."""
+    per_token = {"route": d * s + k * 8 + E * 4, "combine": d * s * (k + 1), "gather_x_bwd": 2 * d * s * 2 * k,
+                 "router_bwd": d * s * (k + 2)}
+    return {n: {"bytes_per_token": b, "ms": stage_ms[n], "tb_per_s": b * T / (stage_ms[n] * 1e-3) / 1e12,
+                "frac_of_hbm_peak": b * T / (stage_ms[n] * 1e-3) / 8e12}
+            for n, b in per_token.items() if stage_ms.get(n, 0) > 0}
+
+
 def cpu_baseline(L, W, sample_tokens):
     """The oracle, as it stands, on the first `sample_tokens` tokens of the batch."""
     from oracle import btx_oracle as O
@@ -124,8 +136,8 @@ def cpu_baseline(L, W, sample_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--tokens", type=int, default=WORKLOAD["T"], help="override T (parity/dev runs only)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
@@ -167,14 +179,18 @@ def main():
 
     n_stage = len(B.STAGE_NAMES)
     events = HipEvents(2 * n_stage * args.steps)
+    step_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for s in range(args.steps):
         ptr, n = events.slice(2 * n_stage * s, n_stage)
         lib.btx_profile_stages(ptr, n)
+        step_ev[s][0].record()
         step()
+        step_ev[s][1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     lib.btx_profile_stages(None, 0)
+    step_ms = sorted(a.elapsed_time(b) for a, b in step_ev)
 
     stage_ms = {}
     for i, name in enumerate(B.STAGE_NAMES):
@@ -206,6 +222,8 @@ def main():
                          "layer_frac_of_peak": 18.0 * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                          "per_kernel": gemm},
         "stage_ms": stage_ms,
+        "step_ms": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},
+        "hbm_stages": hbm_stages(stage_ms, T, d, E, k),
     }
     if args.cpu_sample > 0:
         result["cpu_baseline"] = cpu_baseline(L, W, min(args.cpu_sample, T))
