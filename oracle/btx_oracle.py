@@ -343,6 +343,22 @@ def split_experts(W1: Sequence[np.ndarray], W3: Sequence[np.ndarray], W2: Sequen
     return o1, o3, o2
 
 
+def blend_experts(W1: Sequence[np.ndarray], W3: Sequence[np.ndarray], W2: Sequence[np.ndarray]):
+    """Sec. 3.3 "Blending Experts": every FF is cut along d_ff into N chunks (N = number of
+    FFs) and MoE expert n is built from the n-th chunk of every domain FF, domain after
+    domain.  Width stays d_ff; the hidden units are only dealt out differently."""
+    N = len(W1)
+    f = np.asarray(W1[0]).shape[1]
+    assert f % N == 0
+    fc = f // N
+    o1, o3, o2 = [], [], []
+    for n in range(N):
+        o1.append(np.concatenate([np.asarray(W1[i])[:, n * fc:(n + 1) * fc] for i in range(N)], axis=1))
+        o3.append(np.concatenate([np.asarray(W3[i])[:, n * fc:(n + 1) * fc] for i in range(N)], axis=1))
+        o2.append(np.concatenate([np.asarray(W2[i])[n * fc:(n + 1) * fc, :] for i in range(N)], axis=0))
+    return o1, o3, o2
+
+
 def merge_average(tensors: Sequence[np.ndarray]) -> np.ndarray:
     """Elementwise mean of N same-shape tensors, in float64."""
     acc = np.zeros_like(np.asarray(tensors[0], F64))

@@ -325,6 +325,30 @@ def test_split_chunks_sum_to_the_unsplit_ff():
     np.testing.assert_allclose(out, O.expert_ff(x, W1[0], W3[0], W2[0]) / 3, rtol=1e-11, atol=1e-13)
 
 
+def test_blend_deals_hidden_units_out_without_changing_their_sum():
+    x, _, W1, W3, W2 = tiny_layer(T=5, d=8, f=12, E=3)
+    b1, b3, b2 = O.blend_experts(W1, W3, W2)
+    assert len(b1) == 3 and b1[0].shape == (8, 12) and b2[0].shape == (12, 8)
+    # every hidden unit still exists exactly once: the sum over experts of FF(x) is unchanged
+    total = sum(O.expert_ff(x, W1[i], W3[i], W2[i]) for i in range(3))
+    blended = sum(O.expert_ff(x, b1[n], b3[n], b2[n]) for n in range(3))
+    np.testing.assert_allclose(blended, total, rtol=1e-11, atol=1e-13)
+    # expert n holds chunk n of every domain, domain after domain (f/N = 4 columns each)
+    np.testing.assert_array_equal(b1[1][:, 8:12], np.asarray(W1[2])[:, 4:8])
+    np.testing.assert_array_equal(b2[2][0:4, :], np.asarray(W2[0])[8:12, :])
+    # dealing out twice puts every chunk back
+    c1, c3, c2 = O.blend_experts(b1, b3, b2)
+    for i in range(3):
+        np.testing.assert_array_equal(c1[i], W1[i])
+        np.testing.assert_array_equal(c3[i], W3[i])
+        np.testing.assert_array_equal(c2[i], W2[i])
+    # blended expert = what splitting into N chunks and regrouping by chunk index gives
+    s1, s3, s2 = O.split_experts(W1, W3, W2, 3)
+    for n in range(3):
+        np.testing.assert_array_equal(b1[n], np.concatenate([s1[i * 3 + n] for i in range(3)], axis=1))
+        np.testing.assert_array_equal(b2[n], np.concatenate([s2[i * 3 + n] for i in range(3)], axis=0))
+
+
 def test_merge_average():
     a = RNG.normal(size=(5, 7)).astype(np.float32)
     for n in (1, 2, 3, 4, 7):
