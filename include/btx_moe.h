@@ -211,6 +211,24 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
  */
 int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * btx_mix_experts - MiX construction utilities of Sec. 3.3: "Splitting Experts"
+ * (each of the N FFs is cut along d_ff into C chunks, giving N*C experts of width
+ * f/C: expert i*C+c owns columns [c*f/C, (c+1)*f/C) of W1_i and W3_i and the same
+ * rows of W2_i) and "Blending Experts" (each FF is cut into N chunks and expert n is
+ * built from the n-th chunk of FF 0, FF 1, ... in that order; width stays f).  A
+ * one-off copy made when the MoE is built; every element is moved unchanged.
+ *   W1, W3: DEVICE [N,d,f]; W2: DEVICE [N,f,d]; contiguous, element type `dtype`.
+ *   mode: BTX_MIX_SPLIT (C >= 1, f % C == 0, N*C <= 64) or BTX_MIX_BLEND (C ignored,
+ *         f % N == 0).
+ *   oW1, oW3: DEVICE [N*C,d,f/C] (split) or [N,d,f] (blend); oW2: [N*C,f/C,d] or
+ *         [N,f,d].  Caller-owned, must not be the input buffers.
+ * Errors: BTX_ERR_INVALID_ARG (NULL or aliased pointers, bad mode or chunk count),
+ * BTX_ERR_HIP. */
+typedef enum { BTX_MIX_SPLIT = 0, BTX_MIX_BLEND = 1 } btx_mix_mode;
+int btx_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
+                    void* oW1, void* oW3, void* oW2, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -40,6 +40,7 @@ _SIGNATURES = {
     "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u] + [_vp] * 11 + [_vp] * 6 +
                             [_i, _vp, _sz, _vp]),
     "btx_merge_average": (_i, [ctypes.POINTER(_vp), _i, _vp, _i64, _i, _vp]),
+    "btx_mix_experts": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -228,14 +229,31 @@ def btx_probe_mfma(data: torch.Tensor, n_blocks: int = 256, iters: int = 1000) -
     return flops.value
 
 
-def split_experts(W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, C: int):
-    """Re-index stacked experts [N,d,f] / [N,f,d] into N*C experts of width f/C
-    (Sec. 3.3 "Splitting Experts"): expert i*C+c owns columns c*f/C.. of W1_i, W3_i
-    and the same rows of W2_i.  A one-off layout copy made when the MoE is built."""
+BTX_MIX_SPLIT, BTX_MIX_BLEND = 0, 1
+
+
+def btx_mix_experts(W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, mode: int, C: int = 1):
+    """Stacked experts [N,d,f] / [N,f,d] -> split ([N*C,d,f/C], [N*C,f/C,d]) or blended
+    ([N,d,f], [N,f,d]) copies, made by the library's copy kernels."""
+    lib = load_library()
     N, d, f = W1.shape
-    assert f % C == 0
-    fc = f // C
-    s1 = W1.reshape(N, d, C, fc).permute(0, 2, 1, 3).reshape(N * C, d, fc).contiguous()
-    s3 = W3.reshape(N, d, C, fc).permute(0, 2, 1, 3).reshape(N * C, d, fc).contiguous()
-    s2 = W2.reshape(N * C, fc, d).contiguous()
-    return s1, s3, s2
+    assert W3.shape == W1.shape and W2.shape == (N, f, d) and W1.dtype == W3.dtype == W2.dtype
+    n_out, fo = (N * C, f // max(C, 1)) if mode == BTX_MIX_SPLIT else (N, f)
+    o1 = torch.empty((n_out, d, fo), dtype=W1.dtype, device=W1.device)
+    o3 = torch.empty_like(o1)
+    o2 = torch.empty((n_out, fo, d), dtype=W1.dtype, device=W1.device)
+    st = lib.btx_mix_experts(_ptr(W1), _ptr(W3), _ptr(W2), _dtype_code(W1), N, d, f, mode, C, _ptr(o1), _ptr(o3),
+                             _ptr(o2), _stream())
+    _check(st, "btx_mix_experts")
+    return o1, o3, o2
+
+
+def split_experts(W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, C: int):
+    """Sec. 3.3 "Splitting Experts": expert i*C+c owns columns c*f/C.. of W1_i, W3_i and the
+    same rows of W2_i."""
+    return btx_mix_experts(W1, W3, W2, BTX_MIX_SPLIT, C)
+
+
+def blend_experts(W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor):
+    """Sec. 3.3 "Blending Experts": expert n = the n-th of N chunks of every FF, FF after FF."""
+    return btx_mix_experts(W1, W3, W2, BTX_MIX_BLEND)

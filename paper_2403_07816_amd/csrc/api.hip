@@ -231,5 +231,17 @@ int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel
   return launch_merge_average(inputs, N, out, numel, dtype, static_cast<hipStream_t>(stream));
 }
 
+int btx_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
+                    void* oW1, void* oW3, void* oW2, void* stream) {
+  if (!dtype_ok(dtype) || N < 1 || d < 1 || f < 1) return BTX_ERR_INVALID_ARG;
+  if (mode != BTX_MIX_SPLIT && mode != BTX_MIX_BLEND) return BTX_ERR_INVALID_ARG;
+  const int chunks = mode == BTX_MIX_SPLIT ? C : N;
+  if (chunks < 1 || f % chunks != 0) return BTX_ERR_INVALID_ARG;
+  if (mode == BTX_MIX_SPLIT && (int64_t)N * C > kMaxExperts) return BTX_ERR_INVALID_ARG;
+  if (!W1 || !W3 || !W2 || !oW1 || !oW3 || !oW2) return BTX_ERR_INVALID_ARG;
+  if (W1 == oW1 || W3 == oW3 || W2 == oW2) return BTX_ERR_INVALID_ARG;   // not an in-place operation
+  return launch_mix_experts(W1, W3, W2, dtype, N, d, f, mode, C, oW1, oW3, oW2, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

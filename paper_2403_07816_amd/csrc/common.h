@@ -146,6 +146,8 @@ struct RouterBwdArgs {
 size_t router_bwd_workspace_bytes(int T, int d, int E);
 int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s);
 
+int launch_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
+                       void* oW1, void* oW3, void* oW2, hipStream_t s);
 int launch_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, hipStream_t s);
 
 }  // namespace btx

@@ -101,6 +101,19 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert lib.btx_merge_average(arr, 2, p, -1, 0, null) == 1
 
 
+def test_mix_experts_rejects_bad_arguments(lib):
+    bad = 1
+    a, b, c, x, y, z = (ctypes.c_void_p(0x1000 * i) for i in range(1, 7))
+    ok_tail = (x, y, z, None)
+    assert lib.btx_mix_experts(a, b, c, 1, 4, 64, 96, 0, 5, *ok_tail) == bad      # 96 % 5 != 0
+    assert lib.btx_mix_experts(a, b, c, 1, 4, 64, 96, 2, 3, *ok_tail) == bad      # unknown mode
+    assert lib.btx_mix_experts(a, b, c, 1, 5, 64, 96, 1, 0, *ok_tail) == bad      # blend: 96 % 5 != 0
+    assert lib.btx_mix_experts(a, b, c, 1, 4, 64, 96, 0, 32, *ok_tail) == bad     # 128 experts
+    assert lib.btx_mix_experts(a, b, c, 1, 4, 64, 96, 0, 3, a, y, z, None) == bad  # output aliases input
+    assert lib.btx_mix_experts(None, b, c, 1, 4, 64, 96, 0, 3, *ok_tail) == bad
+    assert lib.btx_mix_experts(a, b, c, 7, 4, 64, 96, 0, 3, *ok_tail) == bad      # dtype
+
+
 def test_probe_rejects_bad_arguments(lib):
     bad = 1  # BTX_ERR_INVALID_ARG
     dummy = ctypes.c_void_p(0x1000)

@@ -170,6 +170,31 @@ def test_merge_in_place():
     assert torch.equal(sets[0], want)
 
 
+# ------------------------------------------------------------- split / blend
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("N,d,f,C", [(4, 64, 96, 3), (2, 40, 36, 2), (3, 24, 30, 5), (1, 16, 64, 8)])
+def test_split_and_blend_match_the_oracle_bit_for_bit(dtype, N, d, f, C):
+    """Pure re-indexing: every element must arrive unchanged, also where the chunk width is
+    not a whole number of 16-byte units (scalar copy path)."""
+    L = synth.make_layer(8, d, f * (N if f % N else 1), N, dtype=dtype)
+    G = to_dev(L)
+    W1, W3, W2 = G["W1"], G["W3"], G["W2"]
+    n1, n3, n2 = experts_np(L["W1"]), experts_np(L["W3"]), experts_np(L["W2"])
+    if W1.shape[2] % C == 0:
+        g1, g3, g2 = B.split_experts(W1, W3, W2, C)
+        o1, o3, o2 = O.split_experts(n1, n3, n2, C)
+        for g, o in ((g1, o1), (g3, o3), (g2, o2)):
+            assert g.shape[0] == N * C
+            assert np.array_equal(to_np(g), np.stack(o))
+    g1, g3, g2 = B.blend_experts(W1, W3, W2)
+    o1, o3, o2 = O.blend_experts(n1, n3, n2)
+    for g, o in ((g1, o1), (g3, o3), (g2, o2)):
+        assert np.array_equal(to_np(g), np.stack(o))
+    # dealing out twice restores the input
+    b1, b3, b2 = B.blend_experts(g1, g3, g2)
+    assert torch.equal(b1, W1) and torch.equal(b3, W3) and torch.equal(b2, W2)
+
+
 # ------------------------------------------------------------ measurement aid
 def test_mfma_probe_runs_and_counts_its_flops():
     data = torch.randn(1 << 20, device="cuda").to(torch.bfloat16)
