@@ -48,6 +48,7 @@ import numpy as np
 ROUTE_TOPK_RENORM = 0
 ROUTE_SWITCH_TOP1 = 1
 ROUTE_SAMPLE_TOP1 = 2
+ROUTE_GUMBEL_TOP1 = 3
 
 LB_TOKEN_FRAC = 0
 LB_GATE_MEAN = 1
@@ -90,16 +91,24 @@ def router_logits(x, W_router, b_router=None) -> np.ndarray:
     return s
 
 
-def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None) -> Dict[str, np.ndarray]:
+def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau: float = 1.0) -> Dict[str, np.ndarray]:
     """Logits, full softmax, chosen experts idx[T,k] and their gates[T,k].
 
     forced_idx[T,k] (entries < 0 = not forced) overrides the selection of
     individual tokens; the gate formulas are then applied to the forced set.
+
+    ROUTE_GUMBEL_TOP1 (Sec. 3.3 "Sample Top-1", training time): U is the Gumbel
+    noise G[T,E] drawn by the caller and tau the temperature; the soft sample is
+    y = softmax((logits + G) / tau), all of it but its largest entry is zeroed,
+    so the gate is that largest entry and only its expert is computed.  "probs"
+    stays the plain softmax of the logits, which is what the load-balancing loss
+    uses; the soft sample is returned as "gate_probs".
     """
     s = router_logits(x, W_router, b_router)
     T, E = s.shape
     assert 1 <= k <= E
     p = softmax(s)
+    gate_probs = None
     if mode == ROUTE_TOPK_RENORM:
         # descending logit, ties -> lower index (stable sort of the negated logits)
         idx = np.argsort(-s, axis=1, kind="stable")[:, :k]
@@ -119,6 +128,11 @@ def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None) -> 
                     chosen = e
                     break
             idx[t, 0] = chosen
+    elif mode == ROUTE_GUMBEL_TOP1:
+        assert k == 1 and U is not None and tau > 0
+        noisy = s + np.asarray(U, F64)
+        gate_probs = softmax(noisy / tau)
+        idx = np.argsort(-noisy, axis=1, kind="stable")[:, :1]
     else:
         raise ValueError("unknown route mode")
     idx = idx.astype(np.int64)
@@ -128,9 +142,14 @@ def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None) -> 
         idx[rows] = forced_idx[rows]
     if mode == ROUTE_TOPK_RENORM:
         gates = softmax(np.take_along_axis(s, idx, axis=1))
+    elif mode == ROUTE_GUMBEL_TOP1:
+        gates = np.take_along_axis(gate_probs, idx, axis=1)
     else:
         gates = np.take_along_axis(p, idx, axis=1)
-    return {"logits": s, "probs": p, "idx": idx, "gates": gates}
+    res = {"logits": s, "probs": p, "idx": idx, "gates": gates}
+    if gate_probs is not None:
+        res["gate_probs"] = gate_probs
+    return res
 
 
 def dense_gates(idx: np.ndarray, gates: np.ndarray, E: int) -> np.ndarray:
@@ -186,14 +205,14 @@ def grouping(idx: np.ndarray, E: int) -> Dict[str, np.ndarray]:
 # --------------------------------------------------------------------------
 def moe_forward(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOPK_RENORM, U=None,
                 alpha: float = 0.0, lb_mode: int = LB_TOKEN_FRAC, forced_idx=None,
-                keep_y: bool = False) -> Dict[str, np.ndarray]:
+                keep_y: bool = False, tau: float = 1.0) -> Dict[str, np.ndarray]:
     """out_t = sum_i g_i(W_l x_t) FF_i(x_t), evaluating FF_i only where the
     gate is non-zero (the paper's own remark that zero-gate experts are
     skipped); W1/W3/W2 are sequences of per-expert matrices."""
     x = np.asarray(x, F64)
     T, d = x.shape
     E = len(W1)
-    r = route(x, W_router, b_router, k, mode, U, forced_idx)
+    r = route(x, W_router, b_router, k, mode, U, forced_idx, tau)
     idx, gates = r["idx"], r["gates"]
     out = np.zeros((T, d), dtype=F64)
     y = np.zeros((T, k, d), dtype=F64) if keep_y else None
@@ -214,12 +233,12 @@ def moe_forward(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOP
 
 
 def moe_forward_all_experts(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOPK_RENORM,
-                            U=None) -> np.ndarray:
+                            U=None, tau: float = 1.0) -> np.ndarray:
     """The layer equation taken literally: every expert on every token, times
     the dense (mostly zero) gate vector.  Used to pin moe_forward."""
     x = np.asarray(x, F64)
     E = len(W1)
-    r = route(x, W_router, b_router, k, mode, U)
+    r = route(x, W_router, b_router, k, mode, U, None, tau)
     g = dense_gates(r["idx"], r["gates"], E)
     out = np.zeros_like(x)
     for e in range(E):
@@ -238,7 +257,7 @@ def lb_grad_logits(probs, u, alpha: float, T_batch: int) -> np.ndarray:
 def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: Dict[str, np.ndarray],
                  alpha: float = 0.0, lb_mode: int = LB_TOKEN_FRAC, lb_grad_scale: float = 0.0,
                  grad_through_u: bool = False, batch_stats: Optional[Dict] = None,
-                 want_dW: bool = True) -> Dict[str, np.ndarray]:
+                 want_dW: bool = True, tau: float = 1.0) -> Dict[str, np.ndarray]:
     """Gradients of  <dY, out> + lb_grad_scale * L_LB  with idx held fixed.
 
     fwd is moe_forward's result for the same inputs (idx, gates, probs are
@@ -293,6 +312,14 @@ def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: 
         for t in range(T):
             for j in range(k):
                 ds[t, idx[t, j]] += ds_sel[t, j]
+    elif mode == ROUTE_GUMBEL_TOP1:
+        # gate = y_e with y = softmax((s + G)/tau): d gate / d s_j = y_e (delta_ej - y_j) / tau
+        yv = fwd["gate_probs"]
+        for t in range(T):
+            e = idx[t, 0]
+            row = -yv[t, e] * yv[t]
+            row[e] += yv[t, e]
+            ds[t] = dg[t, 0] * row / tau
     else:
         for t in range(T):
             e = idx[t, 0]

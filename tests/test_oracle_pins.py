@@ -99,6 +99,45 @@ def test_sample_top1_is_inverse_cdf_and_follows_the_softmax():
     assert r2["idx"][0, 0] == E - 1
 
 
+def test_gumbel_top1_special_cases():
+    """Pins of the Gumbel soft sample (Sec. 3.3): without noise at tau = 1 it is Switch
+    routing; with two experts its gate is a logistic function of the noisy logit gap; a
+    constant added to every noise value changes nothing; a high temperature flattens the gate
+    to 1/E without moving the arg-max; and the chosen expert follows the softmax (Gumbel-max)."""
+    rng = np.random.default_rng(5)
+    x, Wr, W1, W3, W2 = tiny_layer(T=9, d=6, f=5, E=4, rng=rng)
+    b = rng.normal(size=4) * 0.2
+    zero = np.zeros((9, 4))
+    sw = O.route(x, Wr, b, 1, O.ROUTE_SWITCH_TOP1)
+    gz = O.route(x, Wr, b, 1, O.ROUTE_GUMBEL_TOP1, zero, tau=1.0)
+    np.testing.assert_array_equal(gz["idx"], sw["idx"])
+    np.testing.assert_allclose(gz["gates"], sw["gates"], rtol=1e-13)
+    np.testing.assert_allclose(gz["probs"], sw["probs"], rtol=1e-13)
+    G = -np.log(-np.log(rng.random((9, 4))))
+    a = O.route(x, Wr, b, 1, O.ROUTE_GUMBEL_TOP1, G, tau=0.7)
+    c = O.route(x, Wr, b, 1, O.ROUTE_GUMBEL_TOP1, G + 3.25, tau=0.7)
+    np.testing.assert_array_equal(a["idx"], c["idx"])
+    np.testing.assert_allclose(a["gates"], c["gates"], rtol=1e-12)
+    np.testing.assert_allclose(a["probs"], sw["probs"], rtol=1e-13)       # LB probabilities ignore noise and tau
+    np.testing.assert_array_equal(a["idx"][:, 0], np.argmax(a["logits"] + G, axis=1))
+    hot = O.route(x, Wr, b, 1, O.ROUTE_GUMBEL_TOP1, G, tau=1e9)
+    np.testing.assert_array_equal(hot["idx"], a["idx"])
+    np.testing.assert_allclose(hot["gates"], 0.25, rtol=1e-6)
+    # two experts: gate = 1 / (1 + exp(-|gap| / tau))
+    x2, Wr2, *_ = tiny_layer(T=9, d=6, f=5, E=2, rng=rng)
+    G2 = -np.log(-np.log(rng.random((9, 2))))
+    r2 = O.route(x2, Wr2, None, 1, O.ROUTE_GUMBEL_TOP1, G2, tau=0.5)
+    gap = np.abs((r2["logits"] + G2)[:, 0] - (r2["logits"] + G2)[:, 1])
+    np.testing.assert_allclose(r2["gates"][:, 0], 1.0 / (1.0 + np.exp(-gap / 0.5)), rtol=1e-12)
+    # Gumbel-max: arg-max of logits + Gumbel noise is a draw from softmax(logits)
+    s = np.array([[0.3, -1.0, 1.2, 0.1]])
+    n = 40000
+    Gn = -np.log(-np.log(rng.random((n, 4))))
+    picks = np.argmax(s + Gn, axis=1)
+    freq = np.bincount(picks, minlength=4) / n
+    np.testing.assert_allclose(freq, O.softmax(s)[0], atol=0.01)
+
+
 def test_grouping_bruteforce():
     idx = RNG.integers(0, 5, size=(37, 3))
     g = O.grouping(idx, 5)
@@ -218,8 +257,8 @@ def test_lb_uniform_routing_gives_alpha(lb_mode):
 
 
 # --------------------------------------------------------------- backward --
-def _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode):
-    f = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode, forced_idx=forced)
+def _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode, tau=1.0):
+    f = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode, forced_idx=forced, tau=tau)
     L = np.sum(dY * f["out"])
     if lam != 0.0:
         if u_frozen is None:
@@ -236,6 +275,8 @@ def _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb
     (O.ROUTE_SWITCH_TOP1, 1, O.LB_TOKEN_FRAC, False),
     (O.ROUTE_SWITCH_TOP1, 1, O.LB_GATE_MEAN, True),
     (O.ROUTE_SAMPLE_TOP1, 1, O.LB_TOKEN_FRAC, False),
+    (O.ROUTE_GUMBEL_TOP1, 1, O.LB_TOKEN_FRAC, False),
+    (O.ROUTE_GUMBEL_TOP1, 1, O.LB_GATE_MEAN, True),
 ])
 def test_backward_matches_finite_differences(mode, k, lb_mode, through_u):
     rng = np.random.default_rng(11)
@@ -243,12 +284,15 @@ def test_backward_matches_finite_differences(mode, k, lb_mode, through_u):
     x, Wr, W1, W3, W2 = tiny_layer(T, d, f, E, rng=rng)
     b = rng.normal(size=E) * 0.3
     U = rng.random(T)
+    tau = 1.0
+    if mode == O.ROUTE_GUMBEL_TOP1:
+        U, tau = -np.log(-np.log(rng.random((T, E)))), 0.6
     dY = rng.normal(size=(T, d))
     alpha, lam = 0.7, 1.3   # large on purpose so that the LB terms are visible
-    fwd = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode)
+    fwd = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode, tau=tau)
     forced = fwd["idx"].copy()
     u_frozen = None if (through_u or lb_mode == O.LB_TOKEN_FRAC) else fwd["u"].copy()
-    g = O.moe_backward(x, Wr, b, W1, W3, W2, k, mode, dY, fwd, alpha, lb_mode, lam, through_u)
+    g = O.moe_backward(x, Wr, b, W1, W3, W2, k, mode, dY, fwd, alpha, lb_mode, lam, through_u, tau=tau)
 
     def fd(arr, which, setter):
         num = np.zeros_like(arr)
@@ -256,9 +300,9 @@ def test_backward_matches_finite_differences(mode, k, lb_mode, through_u):
         for i in np.ndindex(arr.shape):
             old = arr[i]
             arr[i] = old + eps
-            lp = _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode)
+            lp = _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode, tau)
             arr[i] = old - eps
-            lm = _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode)
+            lm = _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode, tau)
             arr[i] = old
             num[i] = (lp - lm) / (2 * eps)
         return num
