@@ -57,7 +57,11 @@ typedef enum {
   BTX_ROUTE_SWITCH_TOP1 = 1,
   /* Sample top-1: k = 1, expert = first e with cumsum_{j<=e} softmax_j > U[t]
    * (E-1 if none), gate = that expert's full-softmax probability. */
-  BTX_ROUTE_SAMPLE_TOP1 = 2
+  BTX_ROUTE_SAMPLE_TOP1 = 2,
+  /* Sec. 3.3 "Sample Top-1" as printed, training time: soft sample y = softmax((logits + G) / tau)
+   * with Gumbel noise G supplied by the caller, all but its largest entry zeroed: that expert
+   * is run with gate y_max.  The load-balancing probabilities stay softmax(logits). */
+  BTX_ROUTE_GUMBEL_TOP1 = 3
 } btx_route_mode;
 
 /* u_i of the load-balancing loss L_LB = alpha * E * sum_i u_i p_i (Sec. 3.3),
@@ -116,7 +120,9 @@ int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks
  *   x          [T,d]   x_dtype (BTX_F32 or BTX_BF16)
  *   W_router   [d,E]   fp32
  *   b_router   [E]     fp32, may be NULL (the paper's router has no bias)
- *   U          [T]     fp32 in [0,1); required iff route_mode == SAMPLE_TOP1
+ *   U          [T]     fp32 in [0,1); required iff route_mode == SAMPLE_TOP1;
+ *              [T,E]   fp32 Gumbel noise (-log(-log(uniform))) iff route_mode == GUMBEL_TOP1
+ *   tau                temperature of GUMBEL_TOP1 (> 0); ignored by the other modes
  * Selection: logits are accumulated in fp32; ties go to the lower expert index;
  * topk_idx lists the chosen experts by descending logit.
  * Outputs
@@ -131,12 +137,12 @@ int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks
  *   gate_sum   [E]     fp32 sum_t g_{t,e}
  *   prob_sum   [E]     fp32 sum_t softmax_{t,e}
  *   lb_loss    [1]     fp32 lb_alpha * E * sum_e u_e * prob_sum_e / T
- * Requirements: 1 <= k <= E <= 64; d % 8 == 0; SWITCH/SAMPLE need k == 1;
+ * Requirements: 1 <= k <= E <= 64; d % 8 == 0; SWITCH/SAMPLE/GUMBEL need k == 1;
  * T*k < 2^31.  workspace >= btx_moe_route_workspace_bytes(T,E,k).
  */
 size_t btx_moe_route_workspace_bytes(int T, int E, int k);
 int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U,
-                  int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha,
+                  int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau,
                   int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
                   int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss,
                   void* workspace, size_t workspace_bytes, void* stream);
@@ -175,6 +181,9 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
  *   dY [T,d] dtype; x, W*, strides, routing outputs, save_h1/save_h3 as in forward
  *   lb_grad_scale: upstream gradient of lb_loss (1 when it is added to the
  *                  training loss as in Sec. 3.3; 0 = no load-balancing gradient)
+ *   noise [T,E], tau: the Gumbel noise and temperature given to btx_moe_route when
+ *                  route_mode == GUMBEL_TOP1 (the soft sample is recomputed from probs,
+ *                  noise and tau); noise must be NULL for the other modes
  * Outputs (overwritten, never accumulated into)
  *   dX        [T,d]  dtype
  *   dW_router [d,E]  fp32
@@ -188,7 +197,7 @@ size_t btx_moe_ff_backward_workspace_bytes(int T, int d, int f, int E, int k, in
 int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, const void* W1, const void* W3,
                         const void* W2, int dtype, int64_t w13_expert_stride, int64_t w2_expert_stride,
                         int T, int d, int f, int E, int k, int route_mode, int lb_mode, float lb_alpha,
-                        float lb_grad_scale, unsigned flags,
+                        float lb_grad_scale, unsigned flags, const float* noise, float tau,
                         const int32_t* topk_idx, const float* gates, const float* probs,
                         const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos,
                         const float* gate_sum, const float* prob_sum, const int32_t* counts,

@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence, Tuple
 import torch
 
 BTX_F32, BTX_BF16 = 0, 1
-BTX_ROUTE_TOPK_RENORM, BTX_ROUTE_SWITCH_TOP1, BTX_ROUTE_SAMPLE_TOP1 = 0, 1, 2
+BTX_ROUTE_TOPK_RENORM, BTX_ROUTE_SWITCH_TOP1, BTX_ROUTE_SAMPLE_TOP1, BTX_ROUTE_GUMBEL_TOP1 = 0, 1, 2, 3
 BTX_LB_TOKEN_FRAC, BTX_LB_GATE_MEAN = 0, 1
 BTX_FLAG_LB_GRAD_THROUGH_U = 1
 STAGE_NAMES = ["route", "gather_x", "up_swiglu", "down", "combine", "gather_dy", "bwd_act", "bwd_dx", "gather_x_bwd",
@@ -32,12 +32,12 @@ _SIGNATURES = {
     "btx_probe_mfma_out_bytes": (_sz, [_i]),
     "btx_probe_mfma": (_i, [_vp, _sz, _vp, _i, _i, ctypes.POINTER(ctypes.c_double), _vp]),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
-    "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
+    "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),
     "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 3 +
                            [_vp, _sz, _vp]),
     "btx_moe_ff_backward_workspace_bytes": (_sz, [_i] * 6),
-    "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u] + [_vp] * 11 + [_vp] * 6 +
+    "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u, _vp, _f] + [_vp] * 11 + [_vp] * 6 +
                             [_i, _vp, _sz, _vp]),
     "btx_merge_average": (_i, [ctypes.POINTER(_vp), _i, _vp, _i64, _i, _vp]),
     "btx_mix_experts": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
@@ -118,7 +118,8 @@ def alloc_routing(T: int, E: int, k: int, device) -> Routing:
 def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[torch.Tensor] = None,
                   U: Optional[torch.Tensor] = None, k: int = 2, route_mode: int = BTX_ROUTE_TOPK_RENORM,
                   lb_mode: int = BTX_LB_TOKEN_FRAC, lb_alpha: float = 0.0, out: Optional[Routing] = None,
-                  workspace: Optional[torch.Tensor] = None) -> Routing:
+                  workspace: Optional[torch.Tensor] = None, tau: float = 1.0) -> Routing:
+    """U: uniforms [T] for SAMPLE_TOP1, Gumbel noise [T,E] (with temperature tau) for GUMBEL_TOP1."""
     lib = load_library()
     T, d = x.shape
     E = W_router.shape[1]
@@ -126,7 +127,7 @@ def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[to
     r = out if out is not None else alloc_routing(T, E, k, x.device)
     ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), x.device, workspace)
     st = lib.btx_moe_route(_ptr(x), _dtype_code(x), _ptr(W_router), _ptr(b_router), _ptr(U), T, d, E, k, route_mode,
-                           lb_mode, lb_alpha, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
+                           lb_mode, lb_alpha, tau, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
                            _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum),
                            _ptr(r.lb_loss), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_route")
@@ -179,7 +180,8 @@ def btx_moe_ff_backward(dY: torch.Tensor, x: torch.Tensor, W_router: torch.Tenso
                         route_mode: int = BTX_ROUTE_TOPK_RENORM, lb_mode: int = BTX_LB_TOKEN_FRAC,
                         lb_alpha: float = 0.0, lb_grad_scale: float = 0.0, flags: int = 0,
                         dW_dtype: Optional[torch.dtype] = None, frozen_experts: bool = False,
-                        out: Optional[Grads] = None, workspace: Optional[torch.Tensor] = None) -> Grads:
+                        out: Optional[Grads] = None, workspace: Optional[torch.Tensor] = None,
+                        noise: Optional[torch.Tensor] = None, tau: float = 1.0) -> Grads:
     lib = load_library()
     T, d = x.shape
     E, s13 = _stacked(W1)
@@ -195,7 +197,8 @@ def btx_moe_ff_backward(dY: torch.Tensor, x: torch.Tensor, W_router: torch.Tenso
     dwc = BTX_F32 if dW_dtype == torch.float32 else BTX_BF16
     ws = _workspace(lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
     st = lib.btx_moe_ff_backward(_ptr(dY), _ptr(x), _ptr(W_router), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f,
-                                 E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, _ptr(routing.topk_idx),
+                                 E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, _ptr(noise), tau,
+                                 _ptr(routing.topk_idx),
                                  _ptr(routing.gates), _ptr(routing.probs), _ptr(routing.offsets), _ptr(routing.perm),
                                  _ptr(routing.inv_pos), _ptr(routing.gate_sum), _ptr(routing.prob_sum),
                                  _ptr(routing.counts), _ptr(h1), _ptr(h3), _ptr(out.dX), _ptr(out.dW_router),

@@ -112,22 +112,24 @@ size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
 }
 
 int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T, int d,
-                  int E, int k, int route_mode, int lb_mode, float lb_alpha, int32_t* topk_idx, float* gates,
-                  float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
+                  int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau, int32_t* topk_idx,
+                  float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
                   float* prob_sum, float* lb_loss, void* workspace, size_t workspace_bytes, void* stream) {
   if (!dtype_ok(x_dtype) || T < 0 || d <= 0 || d % 8 != 0 || E < 1 || E > kMaxExperts || k < 1 || k > E)
     return BTX_ERR_INVALID_ARG;
   if ((int64_t)T * k >= (int64_t)1 << 31) return BTX_ERR_INVALID_ARG;
-  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_SAMPLE_TOP1) return BTX_ERR_INVALID_ARG;
+  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_GUMBEL_TOP1) return BTX_ERR_INVALID_ARG;
   if (lb_mode != BTX_LB_TOKEN_FRAC && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
   if (route_mode != BTX_ROUTE_TOPK_RENORM && k != 1) return BTX_ERR_INVALID_ARG;
-  if ((route_mode == BTX_ROUTE_SAMPLE_TOP1) != (U != nullptr)) return BTX_ERR_INVALID_ARG;
+  const bool needs_U = route_mode == BTX_ROUTE_SAMPLE_TOP1 || route_mode == BTX_ROUTE_GUMBEL_TOP1;
+  if (needs_U != (U != nullptr)) return BTX_ERR_INVALID_ARG;
+  if (route_mode == BTX_ROUTE_GUMBEL_TOP1 && !(tau > 0.f)) return BTX_ERR_INVALID_ARG;
   if (T == 0) return BTX_OK;
   if (!x || !W_router || !topk_idx || !gates || !probs || !counts || !offsets || !perm || !inv_pos || !gate_sum ||
       !prob_sum || !lb_loss || !workspace)
     return BTX_ERR_INVALID_ARG;
   if (workspace_bytes < route_workspace_bytes(T, E, k)) return BTX_ERR_WORKSPACE;
-  RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, topk_idx, gates, probs,
+  RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, tau, topk_idx, gates, probs,
               counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace};
   hipStream_t s = static_cast<hipStream_t>(stream);
   BTX_STAGE(BTX_STAGE_ROUTE, launch_route(a, s));
@@ -173,7 +175,8 @@ size_t btx_moe_ff_backward_workspace_bytes(int T, int d, int f, int E, int k, in
 int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, const void* W1, const void* W3,
                         const void* W2, int dtype, int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d,
                         int f, int E, int k, int route_mode, int lb_mode, float lb_alpha, float lb_grad_scale,
-                        unsigned flags, const int32_t* topk_idx, const float* gates, const float* probs,
+                        unsigned flags, const float* noise, float tau, const int32_t* topk_idx, const float* gates,
+                        const float* probs,
                         const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos, const float* gate_sum,
                         const float* prob_sum, const int32_t* counts, const void* save_h1, const void* save_h3, void* dX,
                         float* dW_router, float* db_router, void* dW1, void* dW3, void* dW2, int dW_dtype,
@@ -181,8 +184,10 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   if (!dtype_ok(dtype) || !dtype_ok(dW_dtype) || !shapes_ok(T, d, f, E, k)) return BTX_ERR_INVALID_ARG;
   if (dW_dtype != dtype && dW_dtype != BTX_F32) return BTX_ERR_INVALID_ARG;
   if (w13_expert_stride < (int64_t)d * f || w2_expert_stride < (int64_t)d * f) return BTX_ERR_INVALID_ARG;
-  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_SAMPLE_TOP1) return BTX_ERR_INVALID_ARG;
+  if (route_mode < BTX_ROUTE_TOPK_RENORM || route_mode > BTX_ROUTE_GUMBEL_TOP1) return BTX_ERR_INVALID_ARG;
   if (route_mode != BTX_ROUTE_TOPK_RENORM && k != 1) return BTX_ERR_INVALID_ARG;
+  if ((route_mode == BTX_ROUTE_GUMBEL_TOP1) != (noise != nullptr)) return BTX_ERR_INVALID_ARG;
+  if (route_mode == BTX_ROUTE_GUMBEL_TOP1 && !(tau > 0.f)) return BTX_ERR_INVALID_ARG;
   if (lb_mode != BTX_LB_TOKEN_FRAC && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
   if (flags & ~BTX_FLAG_LB_GRAD_THROUGH_U) return BTX_ERR_INVALID_ARG;
   if ((flags & BTX_FLAG_LB_GRAD_THROUGH_U) && lb_mode != BTX_LB_GATE_MEAN) return BTX_ERR_INVALID_ARG;
@@ -215,8 +220,8 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
     BTX_STAGE(BTX_STAGE_DW13, launch_bwd_dw13(dtype, dW_dtype, w.xs, w.dh1, w.dh3, offsets, sh, dW1, dW3, s));
     BTX_STAGE(BTX_STAGE_DW2, launch_bwd_dw2(dtype, dW_dtype, w.ga, tr ? w.dysT : w.dys, offsets, sh, dW2, s));
   }
-  RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, topk_idx,
-                   gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,
+  RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, noise, tau,
+                   topk_idx, gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,
                    dW_router, db_router, w.router};
   BTX_STAGE(BTX_STAGE_ROUTER_BWD, launch_router_bwd(ra, s));
   return BTX_OK;

@@ -87,7 +87,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // ---- internal launchers (one translation unit each) ------------------------
 struct RouteArgs {
   const void* x; int x_dtype; const float* W_router; const float* b_router; const float* U;
-  int T, d, E, k, route_mode, lb_mode; float lb_alpha;
+  int T, d, E, k, route_mode, lb_mode; float lb_alpha, tau;
   int32_t* topk_idx; float* gates; float* probs; int32_t* counts; int32_t* offsets; int32_t* perm;
   int32_t* inv_pos; float* gate_sum; float* prob_sum; float* lb_loss;
   void* workspace;
@@ -139,7 +139,7 @@ size_t ff_scratch_bytes(int dtype, int R, int f);
 
 struct RouterBwdArgs {
   const void* x; int dtype; const float* W_router; int T, d, E, k, route_mode, lb_mode; float lb_alpha, lb_grad_scale;
-  unsigned flags; const int32_t* topk_idx; const float* gates; const float* probs; const int32_t* inv_pos;
+  unsigned flags; const float* noise; float tau; const int32_t* topk_idx; const float* gates; const float* probs; const int32_t* inv_pos;
   const float* gate_sum; const float* prob_sum; const int32_t* counts; const float* dg_part; int n_part;
   const void* dxs; void* dX; float* dW_router; float* db_router; void* workspace;
 };

@@ -72,7 +72,7 @@ __device__ __forceinline__ float wave_incl_scan(float v, int lane) {
 template <typename XT, int EC>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
     const XT* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ br,
-    const float* __restrict__ U, int T, int d, int E, int k, int mode, int32_t* __restrict__ topk_idx,
+    const float* __restrict__ U, int T, int d, int E, int k, int mode, float inv_tau, int32_t* __restrict__ topk_idx,
     float* __restrict__ gates, float* __restrict__ probs, int32_t* __restrict__ blk_counts,
     float* __restrict__ blk_gsum, float* __restrict__ blk_psum) {
   __shared__ float s_logit[kWavesPerBlock][kTokPerWave][kMaxExperts];
@@ -157,8 +157,16 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
       }
     } else {
       int chosen;
+      float g = p;
       if (mode == BTX_ROUTE_SWITCH_TOP1) {
         chosen = wave_best(Best{s, lane}).i;
+      } else if (mode == BTX_ROUTE_GUMBEL_TOP1) {
+        // soft sample softmax((logits + noise) / tau); its largest entry is 1 / sum of the
+        // others' ratios to it, and that entry alone is kept
+        const float noisy = live ? s + U[(size_t)t * E + lane] : -INFINITY;
+        const Best b = wave_best(Best{noisy, lane});
+        chosen = b.i;
+        g = 1.f / wave_sum(live ? __expf((noisy - b.v) * inv_tau) : 0.f);
       } else {
         const float c = wave_incl_scan(p, lane);
         const unsigned long long m = __ballot(live && c > U[t]);
@@ -166,8 +174,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
       }
       if (lane == chosen) {
         topk_idx[t] = lane;
-        gates[t] = p;
-        gsum += p;
+        gates[t] = g;
+        gsum += g;
         cnt += 1;
       }
     }
@@ -309,7 +317,7 @@ void launch_tokens(const RouteArgs& a, int nblk, int32_t* bc, float* bg, float* 
   dim3 grid(nblk), block(kWavesPerBlock * kWave);
 #define BTX_ROUTE_LAUNCH(EC)                                                                                  \
   route_tokens_kernel<XT, EC><<<grid, block, 0, s>>>(x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k,      \
-                                                      a.route_mode, a.topk_idx, a.gates, a.probs, bc, bg, bp)
+                                                      a.route_mode, 1.f / a.tau, a.topk_idx, a.gates, a.probs, bc, bg, bp)
   if (a.E <= 1) BTX_ROUTE_LAUNCH(1);
   else if (a.E <= 2) BTX_ROUTE_LAUNCH(2);
   else if (a.E <= 4) BTX_ROUTE_LAUNCH(4);

@@ -18,6 +18,7 @@ constexpr int kEC = 8;          // experts per dW_router pass
 
 __global__ __launch_bounds__(256) void router_ds_kernel(
     int T, int E, int k, int mode, int lb_mode, float lb_alpha, float lam, unsigned flags,
+    const float* __restrict__ noise, float inv_tau,
     const int32_t* __restrict__ topk_idx, const float* __restrict__ gates, const float* __restrict__ probs,
     const int32_t* __restrict__ inv_pos, const float* __restrict__ gate_sum, const float* __restrict__ prob_sum,
     const int32_t* __restrict__ counts, const float* __restrict__ dg_part, int n_part, float* __restrict__ ds) {
@@ -50,6 +51,19 @@ __global__ __launch_bounds__(256) void router_ds_kernel(
       const float v = __shfl(mine, j, kWave);
       if (lane == e) dsv = v;
     }
+  } else if (mode == BTX_ROUTE_GUMBEL_TOP1) {
+    // gate = y_e, y = softmax((logits + noise) / tau), rebuilt from log p (= logits up to a
+    // constant per token): d gate / d logit_j = y_e (delta_ej - y_j) / tau
+    const int e = __shfl(my_e, 0, kWave);
+    const float dg0 = __shfl(dg, 0, kWave);
+    const float v = live ? (__logf(p) + noise[(size_t)t * E + lane]) * inv_tau : -INFINITY;
+    float vmax = v;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o, kWave));
+    const float z = live ? __expf(v - vmax) : 0.f;
+    const float y = z / wave_sum(z);
+    const float ye = __shfl(y, e, kWave);
+    dsv = dg0 * ye * ((lane == e ? 1.f : 0.f) - y) * inv_tau;
   } else {
     const int e = __shfl(my_e, 0, kWave);
     const float dg0 = __shfl(dg, 0, kWave);
@@ -242,7 +256,8 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
   float* dbp = reinterpret_cast<float*>(w);
 
   router_ds_kernel<<<ceil_div(a.T, 4), 256, 0, s>>>(a.T, a.E, a.k, a.route_mode, a.lb_mode, a.lb_alpha, a.lb_grad_scale,
-                                                   a.flags, a.topk_idx, a.gates, a.probs, a.inv_pos, a.gate_sum,
+                                                   a.flags, a.noise, a.noise ? 1.f / a.tau : 1.f, a.topk_idx, a.gates,
+                                                   a.probs, a.inv_pos, a.gate_sum,
                                                    a.prob_sum, a.counts, a.dg_part, a.n_part, ds);
   BTX_LAUNCH_CHECK();
   dim3 grid(n_chunks(a.T), ceil_div(a.d, 256 * kColsPerThread), ceil_div(a.E, kEC));

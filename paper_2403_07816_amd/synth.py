@@ -48,7 +48,7 @@ def _randn(shape: Sequence[int], std: float, seed: int, stream: int, device: str
 def make_layer(T: int, d: int, f: int, E: int, *, dtype: torch.dtype = torch.float32,
                seed: int = BASE_SEED, device: str = "cpu", unit_rms: bool = False,
                router_E: Optional[int] = None, router_bias: Optional[Sequence[float]] = None,
-               with_dY: bool = False, with_U: bool = False,
+               with_dY: bool = False, with_U: bool = False, with_gumbel: bool = False,
                identical_experts: bool = False, expert_spread: float = 0.1) -> Dict[str, Optional[torch.Tensor]]:
     """Draw one layer's inputs and parameters.
 
@@ -57,7 +57,8 @@ def make_layer(T: int, d: int, f: int, E: int, *, dtype: torch.dtype = torch.flo
     every FFN into chunks afterwards).  identical_experts=True leaves out the
     per-expert perturbation (the sparse-upcycling initialisation); expert_spread
     is the perturbation's std in units of the seed's (0.1 in the workload recipe;
-    1.0 makes the experts nearly unrelated).
+    1.0 makes the experts nearly unrelated).  with_U draws the uniforms [T] of inverse-CDF
+    sampling, with_gumbel standard Gumbel noise [T, router_E] (both stored under "U").
     """
     router_E = E if router_E is None else router_E
     x = _randn((T, d), 1.0, seed, _STREAM["x"], device)
@@ -82,7 +83,11 @@ def make_layer(T: int, d: int, f: int, E: int, *, dtype: torch.dtype = torch.flo
     out["b_router"] = (None if router_bias is None else
                        torch.tensor(list(router_bias), dtype=torch.float32, device=device))
     out["dY"] = _randn((T, d), 0.1, seed, _STREAM["dY"], device).to(dtype) if with_dY else None
-    if with_U:
+    if with_gumbel:
+        g = _generator(seed, _STREAM["U"], device)
+        u = torch.rand((T, router_E), generator=g, device=device, dtype=torch.float32).clamp_(1e-7, 1.0 - 1e-7)
+        out["U"] = -torch.log(-torch.log(u))
+    elif with_U:
         g = _generator(seed, _STREAM["U"], device)
         out["U"] = torch.rand(T, generator=g, device=device, dtype=torch.float32)
     else:

@@ -30,6 +30,7 @@ def to_dev(layer, device="cuda"):
 
 
 def reconcile_routing(idx_gpu: np.ndarray, orc: dict, mode: int, U):
+    # (Gumbel sampling decides on logits + noise: that sum is what has to be a near-tie)
     """Rows where the GPU's ordered selection differs from the oracle's must be
     near-ties (margin < MARGIN on the oracle's fp64 logits).  Returns the
     forced_idx array that makes the oracle follow the GPU on exactly those rows,
@@ -37,6 +38,8 @@ def reconcile_routing(idx_gpu: np.ndarray, orc: dict, mode: int, U):
     idx_o = orc["idx"]
     T, k = idx_o.shape
     s, p = orc["logits"], orc["probs"]
+    if mode == B.BTX_ROUTE_GUMBEL_TOP1:
+        s = s + U
     diff = np.nonzero(np.any(idx_gpu != idx_o, axis=1))[0]
     forced = -np.ones((T, k), dtype=np.int64)
     for t in diff:
@@ -53,13 +56,13 @@ def reconcile_routing(idx_gpu: np.ndarray, orc: dict, mode: int, U):
     return forced, len(diff)
 
 
-def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False):
+def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False, tau=1.0):
     return O.moe_forward(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
                          experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["U"]), alpha, lb_mode,
-                         forced_idx=forced, keep_y=keep_y)
+                         forced_idx=forced, keep_y=keep_y, tau=tau)
 
 
-def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True):
+def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True, tau=1.0):
     """Compare btx_moe_route's outputs with the oracle.  Returns the oracle's forward
     result (near-tie rows forced to the GPU's choice); with full_forward=False only the
     routing part and the statistics are evaluated (what full-size tests can afford)."""
@@ -67,13 +70,13 @@ def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True):
     U = to_np(L["U"])
     x, Wr, b = to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"])
     idx_gpu = r.topk_idx.cpu().numpy().astype(np.int64)
-    orc = O.route(x, Wr, b, k, mode, U)
+    orc = O.route(x, Wr, b, k, mode, U, tau=tau)
     forced, n_forced = reconcile_routing(idx_gpu, orc, mode, U)
     assert n_forced <= max(1, idx_gpu.shape[0] // 1000), f"{n_forced} near-tie rows is implausibly many"
     if full_forward:
-        fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True)
+        fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True, tau=tau)
     else:
-        fwd = O.route(x, Wr, b, k, mode, U, forced_idx=forced) if n_forced else orc
+        fwd = O.route(x, Wr, b, k, mode, U, forced_idx=forced, tau=tau) if n_forced else orc
         fwd.update(O.lb_statistics(fwd["idx"], fwd["gates"], fwd["probs"], alpha, lb_mode))
     fwd["n_forced"] = n_forced
     assert np.array_equal(fwd["idx"], idx_gpu)
@@ -110,11 +113,12 @@ def router_condition(fwd, ref, mode) -> float:
 
 def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_mode=B.BTX_LB_TOKEN_FRAC, alpha=0.01,
                         lam=1.0, flags=0, bias=None, backward=True, seed=synth.BASE_SEED, unit_rms=False,
-                        dW_dtype=None, identical=False, split=1, expert_spread=0.1, check_router_grads=True):
+                        dW_dtype=None, identical=False, split=1, expert_spread=0.1, check_router_grads=True, tau=1.0):
     """One full route -> forward -> backward on the GPU, checked element by element."""
     n_seed = E // split
     L = synth.make_layer(T, d, f * split, n_seed, dtype=dtype, seed=seed, unit_rms=unit_rms, router_E=E,
                          router_bias=bias, with_dY=backward, with_U=(mode == B.BTX_ROUTE_SAMPLE_TOP1),
+                         with_gumbel=(mode == B.BTX_ROUTE_GUMBEL_TOP1),
                          identical_experts=identical, expert_spread=expert_spread)
     G = to_dev(L)
     if split > 1:
@@ -125,17 +129,18 @@ def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
         for name in ("W1", "W3", "W2"):
             assert np.array_equal(to_np(G[name]), to_np(L[name])), "split re-indexing differs"
     tol = TOL[dtype]
-    r = B.btx_moe_route(G["x"], G["W_router"], G["b_router"], G["U"], k, mode, lb_mode, alpha)
-    fwd = check_route(r, L, k, mode, alpha, lb_mode)
+    r = B.btx_moe_route(G["x"], G["W_router"], G["b_router"], G["U"], k, mode, lb_mode, alpha, tau=tau)
+    fwd = check_route(r, L, k, mode, alpha, lb_mode, tau=tau)
     out, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, save=backward)
     assert_close(to_np(out), fwd["out"], tol, "out")
     if not backward:
         return
     g = B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, mode, lb_mode,
-                              alpha, lam, flags, dW_dtype=dW_dtype)
+                              alpha, lam, flags, dW_dtype=dW_dtype,
+                              noise=G["U"] if mode == B.BTX_ROUTE_GUMBEL_TOP1 else None, tau=tau)
     ref = O.moe_backward(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
                          experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["dY"]), fwd, alpha, lb_mode, lam,
-                         bool(flags & B.BTX_FLAG_LB_GRAD_THROUGH_U))
+                         bool(flags & B.BTX_FLAG_LB_GRAD_THROUGH_U), tau=tau)
     assert_close(to_np(g.dX), ref["dX"], tol, "dX")
     if check_router_grads:
         # fp32: the plain bar.  bf16: the bar times the oracle-computed amplification of

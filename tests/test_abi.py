@@ -46,15 +46,17 @@ def test_route_rejects_bad_arguments(lib):
     p = ctypes.c_void_p(256)   # never dereferenced: validation fails first
     null = None
 
-    def route(T=8, d=64, E=4, k=2, mode=0, lb=0, U=null, x=p, ws_bytes=1 << 20, dtype=0):
-        return lib.btx_moe_route(x, dtype, p, null, U, T, d, E, k, mode, lb, 0.0, p, p, p, p, p, p, p, p, p, p, p,
+    def route(T=8, d=64, E=4, k=2, mode=0, lb=0, U=null, x=p, ws_bytes=1 << 20, dtype=0, tau=1.0):
+        return lib.btx_moe_route(x, dtype, p, null, U, T, d, E, k, mode, lb, 0.0, tau, p, p, p, p, p, p, p, p, p, p, p,
                                  ws_bytes, null)
 
     assert route(k=5) == 1                 # k > E
     assert route(k=0) == 1
     assert route(E=65, k=1) == 1           # more experts than a wavefront has lanes
     assert route(d=60) == 1                # d not a multiple of 8
-    assert route(mode=3) == 1
+    assert route(mode=4) == 1
+    assert route(mode=3, k=1) == 1         # Gumbel sampling needs its noise
+    assert route(mode=3, k=1, U=p, tau=0.0) == 1   # and a positive temperature
     assert route(mode=1, k=2) == 1         # Switch needs k = 1
     assert route(mode=2, k=1) == 1         # sampling needs U
     assert route(mode=0, U=p) == 1         # U only with sampling
@@ -80,9 +82,10 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert fwd(ws=0) == 3
     assert fwd(T=0) == 0
 
-    def bwd(T=8, k=2, mode=0, lb=0, flags=0, dW=(p, p, p), dwt=0, dt=0, ws=1 << 30):
+    def bwd(T=8, k=2, mode=0, lb=0, flags=0, dW=(p, p, p), dwt=0, dt=0, ws=1 << 30, noise=null, tau=1.0):
         return lib.btx_moe_ff_backward(p, p, p, p, p, p, dt, 64 * 64, 64 * 64, T, 64, 64, 4, k, mode, lb, 0.0, 0.0,
-                                       flags, p, p, p, p, p, p, p, p, p, p, p, p, p, null, dW[0], dW[1], dW[2], dwt,
+                                       flags, noise, tau, p, p, p, p, p, p, p, p, p, p, p, p, p, null, dW[0], dW[1],
+                                       dW[2], dwt,
                                        p, ws, null)
 
     assert bwd(dW=(p, null, p)) == 1       # weight gradients: all three or none
@@ -90,6 +93,9 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert bwd(flags=8) == 1
     assert bwd(dt=0, dwt=1) == 1           # fp32 layer cannot return bf16 weight gradients
     assert bwd(mode=1, k=2) == 1
+    assert bwd(mode=3, k=1) == 1           # Gumbel backward needs the noise again
+    assert bwd(mode=0, noise=p) == 1       # and no other mode takes it
+    assert bwd(mode=3, k=1, noise=p, tau=-1.0) == 1
     assert bwd(ws=0) == 3
     assert bwd(T=0) == 0
 

@@ -48,6 +48,23 @@ def test_topk_load_balancing_variants_fp32(lb_mode, flags, lam):
     run_layer_and_check(600, 64, 96, 6, 2, F32, lb_mode=lb_mode, flags=flags, lam=lam, alpha=5.0)
 
 
+@pytest.mark.parametrize("tau", [1.0, 0.5, 3.0])
+@pytest.mark.parametrize("lb_mode,flags", [(B.BTX_LB_TOKEN_FRAC, 0), (B.BTX_LB_GATE_MEAN, B.BTX_FLAG_LB_GRAD_THROUGH_U)])
+def test_gumbel_sample_top1_fp32(tau, lb_mode, flags):
+    run_layer_and_check(301, 72, 88, 5, 1, F32, mode=B.BTX_ROUTE_GUMBEL_TOP1, lb_mode=lb_mode, flags=flags,
+                        bias=[0.5, 0, -0.5, 0, 0.2], tau=tau)
+
+
+def test_gumbel_without_noise_at_unit_temperature_is_switch_routing():
+    L = synth.make_layer(257, 64, 64, 4, dtype=F32, with_dY=True)
+    G = to_dev(L)
+    zero = torch.zeros((257, 4), device="cuda")
+    a = B.btx_moe_route(G["x"], G["W_router"], None, zero, 1, B.BTX_ROUTE_GUMBEL_TOP1, tau=1.0)
+    b = B.btx_moe_route(G["x"], G["W_router"], None, None, 1, B.BTX_ROUTE_SWITCH_TOP1)
+    assert torch.equal(a.topk_idx, b.topk_idx) and torch.equal(a.perm, b.perm)
+    assert_close(a.gates.cpu().numpy(), b.gates.cpu().numpy().astype(np.float64), 1e-6, "gates")
+
+
 def test_expert_without_tokens_fp32():
     """A strongly negative bias starves expert 2: empty group, zero weight gradients."""
     G, r, out, g = run_layer_and_check(300, 64, 80, 4, 2, F32, bias=[0, 0, -60.0, 0])
@@ -133,6 +150,10 @@ def test_bf16_switch_imbalanced():
 
 def test_bf16_sample_top1_imbalanced():
     run_layer_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_SAMPLE_TOP1, bias=[2.0, 0, 0, 0], unit_rms=True)
+
+
+def test_bf16_gumbel_sample_top1():
+    run_layer_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_GUMBEL_TOP1, unit_rms=True, tau=0.5)
 
 
 def test_bf16_expert_without_tokens():
