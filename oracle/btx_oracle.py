@@ -41,6 +41,7 @@ Readings where the paper is silent (also listed in the design notes):
 """
 from __future__ import annotations
 
+import math
 from typing import Dict, List, Optional, Sequence
 
 import numpy as np
@@ -91,7 +92,34 @@ def router_logits(x, W_router, b_router=None) -> np.ndarray:
     return s
 
 
-def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau: float = 1.0) -> Dict[str, np.ndarray]:
+def capacity(T: int, k: int, E: int, capacity_factor: float) -> int:
+    """Rows an expert may take: ceil(capacity_factor * T*k / E) (Sec. 4.3: "a hard limit
+    after which routed tokens will be dropped"); 0 = no limit."""
+    if capacity_factor <= 0:
+        return 0
+    return int(math.ceil(float(capacity_factor) * T * k / E))
+
+
+def dropped_pairs(idx: np.ndarray, E: int, cap: int) -> np.ndarray:
+    """dropped[t,j]: the pair (t,j) is beyond its expert's capacity.  Pairs are served in
+    (t, j) order, so the first `cap` pairs of every expert are kept."""
+    T, k = idx.shape
+    dropped = np.zeros((T, k), dtype=bool)
+    if cap <= 0:
+        return dropped
+    taken = np.zeros(E, dtype=np.int64)
+    for t in range(T):
+        for j in range(k):
+            e = idx[t, j]
+            if taken[e] >= cap:
+                dropped[t, j] = True
+            else:
+                taken[e] += 1
+    return dropped
+
+
+def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau: float = 1.0,
+          capacity_factor: float = 0.0) -> Dict[str, np.ndarray]:
     """Logits, full softmax, chosen experts idx[T,k] and their gates[T,k].
 
     forced_idx[T,k] (entries < 0 = not forced) overrides the selection of
@@ -146,7 +174,8 @@ def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau
         gates = np.take_along_axis(gate_probs, idx, axis=1)
     else:
         gates = np.take_along_axis(p, idx, axis=1)
-    res = {"logits": s, "probs": p, "idx": idx, "gates": gates}
+    res = {"logits": s, "probs": p, "idx": idx, "gates": gates,
+           "dropped": dropped_pairs(idx, E, capacity(T, k, E, capacity_factor))}
     if gate_probs is not None:
         res["gate_probs"] = gate_probs
     return res
@@ -186,16 +215,18 @@ def lb_statistics(idx, gates, probs, alpha: float, lb_mode: int) -> Dict[str, np
             "lb_loss": loss}
 
 
-def grouping(idx: np.ndarray, E: int) -> Dict[str, np.ndarray]:
-    """Group the T*k (token, slot) pairs by expert, keeping (t, j) order inside
-    a group.  perm[r] = t*k+j of the pair at grouped row r; inv_pos[t,j] = r;
-    offsets[e] = first grouped row of expert e."""
+def grouping(idx: np.ndarray, E: int, dropped: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """Group the kept (token, slot) pairs by expert, keeping (t, j) order inside
+    a group.  perm[r] = t*k+j of the pair at grouped row r; inv_pos[t,j] = r, or -1
+    for a dropped pair; offsets[e] = first grouped row of expert e."""
     T, k = idx.shape
     flat = idx.reshape(-1)
-    perm = np.argsort(flat, kind="stable").astype(np.int64)
-    inv = np.empty(T * k, dtype=np.int64)
-    inv[perm] = np.arange(T * k)
-    counts = np.bincount(flat, minlength=E)
+    keep = np.ones(T * k, dtype=bool) if dropped is None else ~np.asarray(dropped).reshape(-1)
+    order = np.argsort(flat, kind="stable").astype(np.int64)
+    perm = order[keep[order]]
+    inv = -np.ones(T * k, dtype=np.int64)
+    inv[perm] = np.arange(perm.size)
+    counts = np.bincount(flat[keep], minlength=E)
     offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
     return {"offsets": offsets, "perm": perm, "inv_pos": inv.reshape(T, k)}
 
@@ -205,19 +236,21 @@ def grouping(idx: np.ndarray, E: int) -> Dict[str, np.ndarray]:
 # --------------------------------------------------------------------------
 def moe_forward(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOPK_RENORM, U=None,
                 alpha: float = 0.0, lb_mode: int = LB_TOKEN_FRAC, forced_idx=None,
-                keep_y: bool = False, tau: float = 1.0) -> Dict[str, np.ndarray]:
+                keep_y: bool = False, tau: float = 1.0, capacity_factor: float = 0.0) -> Dict[str, np.ndarray]:
     """out_t = sum_i g_i(W_l x_t) FF_i(x_t), evaluating FF_i only where the
     gate is non-zero (the paper's own remark that zero-gate experts are
-    skipped); W1/W3/W2 are sequences of per-expert matrices."""
+    skipped); W1/W3/W2 are sequences of per-expert matrices.  With a capacity
+    factor the pairs beyond an expert's capacity contribute nothing."""
     x = np.asarray(x, F64)
     T, d = x.shape
     E = len(W1)
-    r = route(x, W_router, b_router, k, mode, U, forced_idx, tau)
+    r = route(x, W_router, b_router, k, mode, U, forced_idx, tau, capacity_factor)
     idx, gates = r["idx"], r["gates"]
+    kept = ~r["dropped"]
     out = np.zeros((T, d), dtype=F64)
     y = np.zeros((T, k, d), dtype=F64) if keep_y else None
     for e in range(E):
-        tt, jj = np.nonzero(idx == e)
+        tt, jj = np.nonzero((idx == e) & kept)
         if tt.size == 0:
             continue
         ye = expert_ff(x[tt], W1[e], W3[e], W2[e])
@@ -269,6 +302,7 @@ def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: 
     T, d = x.shape
     E = len(W1)
     idx, gates, probs = fwd["idx"], fwd["gates"], fwd["probs"]
+    kept = ~fwd["dropped"] if "dropped" in fwd else np.ones(idx.shape, dtype=bool)
     Wr = np.asarray(W_router, F64)
     if batch_stats is None:
         st = lb_statistics(idx, gates, probs, alpha, lb_mode)
@@ -283,7 +317,7 @@ def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: 
     dW2: List[Optional[np.ndarray]] = [None] * E
     for e in range(E):
         W1e, W3e, W2e = np.asarray(W1[e], F64), np.asarray(W3[e], F64), np.asarray(W2[e], F64)
-        tt, jj = np.nonzero(idx == e)
+        tt, jj = np.nonzero((idx == e) & kept)   # a dropped pair has no output, hence dg = 0
         xe = x[tt]
         h1 = xe @ W1e
         h3 = xe @ W3e

@@ -257,8 +257,9 @@ def test_lb_uniform_routing_gives_alpha(lb_mode):
 
 
 # --------------------------------------------------------------- backward --
-def _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode, tau=1.0):
-    f = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode, forced_idx=forced, tau=tau)
+def _loss(x, Wr, b, W1, W3, W2, k, mode, U, dY, forced, alpha, lam, u_frozen, lb_mode, tau=1.0, cf=0.0):
+    f = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, U, alpha, lb_mode, forced_idx=forced, tau=tau,
+                      capacity_factor=cf)
     L = np.sum(dY * f["out"])
     if lam != 0.0:
         if u_frozen is None:
@@ -315,6 +316,81 @@ def test_backward_matches_finite_differences(mode, k, lb_mode, through_u):
             np.testing.assert_allclose(g["dW1"][e], fd(W1[e], "W1", None), rtol=2e-6, atol=2e-8)
             np.testing.assert_allclose(g["dW3"][e], fd(W3[e], "W3", None), rtol=2e-6, atol=2e-8)
             np.testing.assert_allclose(g["dW2"][e], fd(W2[e], "W2", None), rtol=2e-6, atol=2e-8)
+
+
+def test_capacity_keeps_the_first_pairs_of_every_expert():
+    """Sec. 4.3: a hard limit after which routed tokens are dropped.  Pins: the limit itself,
+    service in (token, slot) order, a dropped pair adds nothing to the output, and a limit
+    nobody reaches changes nothing."""
+    assert O.capacity(10, 1, 4, 1.5) == 4 and O.capacity(16, 2, 4, 1.0) == 8 and O.capacity(7, 1, 4, 0.0) == 0
+    rng = np.random.default_rng(3)
+    x, Wr, W1, W3, W2 = tiny_layer(T=10, d=6, f=5, E=4, rng=rng)
+    b = np.array([9.0, 0.0, 0.0, 0.0])          # everybody wants expert 0
+    r = O.route(x, Wr, b, 1, O.ROUTE_SWITCH_TOP1, capacity_factor=1.5)
+    assert np.all(r["idx"] == 0)
+    np.testing.assert_array_equal(r["dropped"][:, 0], np.arange(10) >= 4)
+    f = O.moe_forward(x, Wr, b, W1, W3, W2, 1, O.ROUTE_SWITCH_TOP1, capacity_factor=1.5)
+    assert not f["out"][4:].any()
+    np.testing.assert_allclose(f["out"][:4], f["gates"][:4] * O.expert_ff(x[:4], W1[0], W3[0], W2[0]), rtol=1e-12)
+    np.testing.assert_array_equal(f["counts"], [10, 0, 0, 0])        # statistics see the routing, not the drops
+    g = O.grouping(r["idx"], 4, r["dropped"])
+    np.testing.assert_array_equal(g["offsets"], [0, 4, 4, 4, 4])
+    np.testing.assert_array_equal(g["perm"], [0, 1, 2, 3])
+    np.testing.assert_array_equal(g["inv_pos"][:, 0], [0, 1, 2, 3] + [-1] * 6)
+    # top-2 in (t, j) order, brute force against the dense layer equation with dropped gates zeroed
+    x, Wr, W1, W3, W2 = tiny_layer(T=9, d=6, f=5, E=3, rng=rng)
+    r = O.route(x, Wr, None, 2, O.ROUTE_TOPK_RENORM, capacity_factor=0.5)
+    cap = O.capacity(9, 2, 3, 0.5)
+    assert cap == 3
+    seen = np.zeros(3, dtype=int)
+    for t in range(9):
+        for j in range(2):
+            e = r["idx"][t, j]
+            assert r["dropped"][t, j] == (seen[e] >= cap)
+            seen[e] += not r["dropped"][t, j]
+    f = O.moe_forward(x, Wr, None, W1, W3, W2, 2, capacity_factor=0.5)
+    dense = O.dense_gates(r["idx"], np.where(r["dropped"], 0.0, r["gates"]), 3)
+    want = sum(dense[:, e:e + 1] * O.expert_ff(x, W1[e], W3[e], W2[e]) for e in range(3))
+    np.testing.assert_allclose(f["out"], want, rtol=1e-12, atol=1e-14)
+    # a limit nobody reaches
+    a = O.moe_forward(x, Wr, None, W1, W3, W2, 2, capacity_factor=3.0)
+    z = O.moe_forward(x, Wr, None, W1, W3, W2, 2)
+    assert not a["dropped"].any()
+    np.testing.assert_array_equal(a["out"], z["out"])
+
+
+@pytest.mark.parametrize("mode,k,cf", [(O.ROUTE_SWITCH_TOP1, 1, 0.75), (O.ROUTE_TOPK_RENORM, 2, 0.5)])
+def test_backward_with_dropped_pairs_matches_finite_differences(mode, k, cf):
+    rng = np.random.default_rng(17)
+    T, d, f, E = 8, 5, 6, 3
+    x, Wr, W1, W3, W2 = tiny_layer(T, d, f, E, rng=rng)
+    b = rng.normal(size=E) * 0.3
+    dY = rng.normal(size=(T, d))
+    alpha, lam = 0.7, 1.3
+    fwd = O.moe_forward(x, Wr, b, W1, W3, W2, k, mode, None, alpha, O.LB_TOKEN_FRAC, capacity_factor=cf)
+    assert fwd["dropped"].any() and not fwd["dropped"].all()
+    forced = fwd["idx"].copy()
+    g = O.moe_backward(x, Wr, b, W1, W3, W2, k, mode, dY, fwd, alpha, O.LB_TOKEN_FRAC, lam)
+
+    def fd(arr):
+        num = np.zeros_like(arr)
+        eps = 1e-6
+        for i in np.ndindex(arr.shape):
+            old = arr[i]
+            arr[i] = old + eps
+            lp = _loss(x, Wr, b, W1, W3, W2, k, mode, None, dY, forced, alpha, lam, None, O.LB_TOKEN_FRAC, cf=cf)
+            arr[i] = old - eps
+            lm = _loss(x, Wr, b, W1, W3, W2, k, mode, None, dY, forced, alpha, lam, None, O.LB_TOKEN_FRAC, cf=cf)
+            arr[i] = old
+            num[i] = (lp - lm) / (2 * eps)
+        return num
+
+    np.testing.assert_allclose(g["dX"], fd(x), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(g["dW_router"], fd(Wr), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(g["db_router"], fd(b), rtol=2e-6, atol=2e-8)
+    for e in range(E):
+        np.testing.assert_allclose(g["dW1"][e], fd(W1[e]), rtol=2e-6, atol=2e-8)
+        np.testing.assert_allclose(g["dW2"][e], fd(W2[e]), rtol=2e-6, atol=2e-8)
 
 
 def test_dW_columns_agrees_with_full_backward_definition_by_loops():
