@@ -123,17 +123,23 @@ int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks
  *   U          [T]     fp32 in [0,1); required iff route_mode == SAMPLE_TOP1;
  *              [T,E]   fp32 Gumbel noise (-log(-log(uniform))) iff route_mode == GUMBEL_TOP1
  *   tau                temperature of GUMBEL_TOP1 (> 0); ignored by the other modes
+ *   capacity_factor    0 = dropless.  > 0: every expert keeps its first
+ *                      ceil(capacity_factor * T*k / E) pairs in (t,j) order (Sec. 4.3: "a hard
+ *                      limit after which routed tokens will be dropped"); a dropped pair gets
+ *                      inv_pos = -1, no grouped row and contributes nothing to the layer's output
+ *                      or to dg; counts, gate_sum and lb_loss describe the routing before drops,
+ *                      offsets the kept rows; perm[r] = 0 for r >= offsets[E]
  * Selection: logits are accumulated in fp32; ties go to the lower expert index;
  * topk_idx lists the chosen experts by descending logit.
  * Outputs
  *   topk_idx   [T,k]   int32 expert ids
  *   gates      [T,k]   fp32
  *   probs      [T,E]   fp32 full softmax (kept for the backward pass)
- *   counts     [E]     int32 routed rows per expert
+ *   counts     [E]     int32 routed pairs per expert (before any capacity drop)
  *   offsets    [E+1]   int32 exclusive prefix of counts
  *   perm       [R]     int32: perm[r] = t*k+j of the pair stored at grouped row r;
  *                      rows of expert e are offsets[e]..offsets[e+1]-1, in (t,j) order
- *   inv_pos    [T,k]   int32: inverse of perm
+ *   inv_pos    [T,k]   int32: inverse of perm (-1: pair dropped)
  *   gate_sum   [E]     fp32 sum_t g_{t,e}
  *   prob_sum   [E]     fp32 sum_t softmax_{t,e}
  *   lb_loss    [1]     fp32 lb_alpha * E * sum_e u_e * prob_sum_e / T
@@ -143,7 +149,7 @@ int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks
 size_t btx_moe_route_workspace_bytes(int T, int E, int k);
 int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U,
                   int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau,
-                  int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
+                  float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
                   int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss,
                   void* workspace, size_t workspace_bytes, void* stream);
 

@@ -32,7 +32,7 @@ _SIGNATURES = {
     "btx_probe_mfma_out_bytes": (_sz, [_i]),
     "btx_probe_mfma": (_i, [_vp, _sz, _vp, _i, _i, ctypes.POINTER(ctypes.c_double), _vp]),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
-    "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
+    "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),
     "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 3 +
                            [_vp, _sz, _vp]),
@@ -118,7 +118,8 @@ def alloc_routing(T: int, E: int, k: int, device) -> Routing:
 def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[torch.Tensor] = None,
                   U: Optional[torch.Tensor] = None, k: int = 2, route_mode: int = BTX_ROUTE_TOPK_RENORM,
                   lb_mode: int = BTX_LB_TOKEN_FRAC, lb_alpha: float = 0.0, out: Optional[Routing] = None,
-                  workspace: Optional[torch.Tensor] = None, tau: float = 1.0) -> Routing:
+                  workspace: Optional[torch.Tensor] = None, tau: float = 1.0,
+                  capacity_factor: float = 0.0) -> Routing:
     """U: uniforms [T] for SAMPLE_TOP1, Gumbel noise [T,E] (with temperature tau) for GUMBEL_TOP1."""
     lib = load_library()
     T, d = x.shape
@@ -127,7 +128,7 @@ def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[to
     r = out if out is not None else alloc_routing(T, E, k, x.device)
     ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), x.device, workspace)
     st = lib.btx_moe_route(_ptr(x), _dtype_code(x), _ptr(W_router), _ptr(b_router), _ptr(U), T, d, E, k, route_mode,
-                           lb_mode, lb_alpha, tau, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
+                           lb_mode, lb_alpha, tau, capacity_factor, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
                            _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum),
                            _ptr(r.lb_loss), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_route")

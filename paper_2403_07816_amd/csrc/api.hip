@@ -1,5 +1,7 @@
 // C ABI of the library: argument validation, workspace carving, and the order in which
 // the stages of the layer are enqueued.  See include/btx_moe.h for the contract.
+#include <cmath>
+
 #include "common.h"
 
 using namespace btx;
@@ -112,8 +114,8 @@ size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
 }
 
 int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T, int d,
-                  int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau, int32_t* topk_idx,
-                  float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
+                  int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
+                  int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
                   float* prob_sum, float* lb_loss, void* workspace, size_t workspace_bytes, void* stream) {
   if (!dtype_ok(x_dtype) || T < 0 || d <= 0 || d % 8 != 0 || E < 1 || E > kMaxExperts || k < 1 || k > E)
     return BTX_ERR_INVALID_ARG;
@@ -124,12 +126,16 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
   const bool needs_U = route_mode == BTX_ROUTE_SAMPLE_TOP1 || route_mode == BTX_ROUTE_GUMBEL_TOP1;
   if (needs_U != (U != nullptr)) return BTX_ERR_INVALID_ARG;
   if (route_mode == BTX_ROUTE_GUMBEL_TOP1 && !(tau > 0.f)) return BTX_ERR_INVALID_ARG;
+  if (!(capacity_factor >= 0.f)) return BTX_ERR_INVALID_ARG;
   if (T == 0) return BTX_OK;
   if (!x || !W_router || !topk_idx || !gates || !probs || !counts || !offsets || !perm || !inv_pos || !gate_sum ||
       !prob_sum || !lb_loss || !workspace)
     return BTX_ERR_INVALID_ARG;
   if (workspace_bytes < route_workspace_bytes(T, E, k)) return BTX_ERR_WORKSPACE;
-  RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, tau, topk_idx, gates, probs,
+  // capacity in double, as the specification of the limit is ceil(cf * T*k / E) over the reals
+  const double cap_d = capacity_factor > 0.f ? std::ceil((double)capacity_factor * T * k / E) : 0.0;
+  const int cap = cap_d > (double)T * k ? T * k : (int)cap_d;
+  RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, tau, cap, topk_idx, gates, probs,
               counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace};
   hipStream_t s = static_cast<hipStream_t>(stream);
   BTX_STAGE(BTX_STAGE_ROUTE, launch_route(a, s));

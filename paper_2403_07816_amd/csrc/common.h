@@ -87,7 +87,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // ---- internal launchers (one translation unit each) ------------------------
 struct RouteArgs {
   const void* x; int x_dtype; const float* W_router; const float* b_router; const float* U;
-  int T, d, E, k, route_mode, lb_mode; float lb_alpha, tau;
+  int T, d, E, k, route_mode, lb_mode; float lb_alpha, tau; int cap;   // cap: rows an expert keeps (0 = all)
   int32_t* topk_idx; float* gates; float* probs; int32_t* counts; int32_t* offsets; int32_t* perm;
   int32_t* inv_pos; float* gate_sum; float* prob_sum; float* lb_loss;
   void* workspace;
@@ -101,7 +101,7 @@ int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, i
 // multiple of 64 (P_e = padded rows of the experts before e); dst is [d][pitch]
 int launch_gather_rows_t(const void* src, void* dst, const int32_t* perm, const int32_t* offsets, int R, int k, int d,
                          int E, int pitch, hipStream_t s);
-// out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]   (gates NULL => unit weights)
+// out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]   (gates NULL => unit weights; inv_pos < 0: dropped pair, skipped)
 int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d,
                    int dtype, hipStream_t s);
 

@@ -113,6 +113,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restri
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
     for (int j = 0; j < k; ++j) {
       const int r = inv_pos[(size_t)t * k + j];
+      if (r < 0) continue;                  // pair dropped at its expert's capacity
       const float g = gates ? gates[(size_t)t * k + j] : 1.f;
       float v[N];
       Chunk<ET>::unpack(y[(size_t)r * chunks_per_row + c], v);

@@ -224,10 +224,11 @@ __device__ __forceinline__ int block_excl_scan(int v, int& total, int* s_wave) {
 }
 
 __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
-    int nblk, int T, int E, int k, int lb_mode, float lb_alpha, const int32_t* __restrict__ blk_counts,
+    int nblk, int T, int E, int k, int cap, int lb_mode, float lb_alpha, const int32_t* __restrict__ blk_counts,
     const float* __restrict__ blk_gsum, const float* __restrict__ blk_psum, int32_t* __restrict__ blk_base,
     int32_t* __restrict__ counts, int32_t* __restrict__ offsets, float* __restrict__ gate_sum,
-    float* __restrict__ prob_sum, float* __restrict__ lb_loss) {
+    float* __restrict__ prob_sum, float* __restrict__ lb_loss, int32_t* __restrict__ perm) {
+  __shared__ int s_kept_total;
   __shared__ int s_wave[kScanThreads / kWave];
   __shared__ int s_count[kMaxExperts];
   __shared__ float s_red[2][kScanThreads / kWave];
@@ -272,23 +273,30 @@ __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
       prob_sum[e] = s_p[e];
       const float u = lb_mode == BTX_LB_TOKEN_FRAC ? (float)s_count[e] / ((float)T * (float)k) : s_g[e] / (float)T;
       loss += u * (s_p[e] / (float)T);
-      off += s_count[e];
+      // capacity: an expert keeps its first `cap` pairs; the statistics above see the routing
+      off += cap > 0 ? min(s_count[e], cap) : s_count[e];
     }
     offsets[E] = off;
     *lb_loss = lb_alpha * (float)E * loss;
+    s_kept_total = off;
   }
+  __syncthreads();
+  // grouped rows past the kept ones do not exist; whoever indexes through perm there
+  // (kernels that run over all T*k rows) must still find a valid pair
+  for (int r = s_kept_total + threadIdx.x; r < T * k; r += kScanThreads) perm[r] = 0;
 }
 
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_scatter_kernel(
-    int nblk, int T, int E, int k, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_base,
+    int nblk, int T, int E, int k, int cap, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_base,
     const int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_pos) {
   const int lane = threadIdx.x & (kWave - 1);
   const int b = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;  // one wavefront per token block
   if (b >= nblk) return;
   const int first = b * kTokPerBlock * k;
   const int last = min((b + 1) * kTokPerBlock, T) * k;
-  // lane e carries the next free grouped row of expert e for this block
-  int next = lane < E ? offsets[lane] + blk_base[(size_t)b * E + lane] : 0;
+  // lane e carries the rank, inside expert e's pairs, of the next pair of this block
+  int next = lane < E ? blk_base[(size_t)b * E + lane] : 0;
+  const int group0 = lane < E ? offsets[lane] : 0;
   for (int i0 = first; i0 < last; i0 += kWave) {
     const int i = i0 + lane;
     const bool valid = i < last;
@@ -297,16 +305,21 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_scatter_kernel(
     for (int q = 0; q < E; ++q) {
       const unsigned long long m = __ballot(e == q);
       const int start = __shfl(next, q, kWave);
+      const int row0 = __shfl(group0, q, kWave);
       if (e == q) {
-        rank = __popcll(m & ((1ull << lane) - 1ull));
-        base = start;
+        rank = start + __popcll(m & ((1ull << lane) - 1ull));
+        base = row0;
       }
       if (lane == q) next += __popcll(m);
     }
     if (valid) {
-      const int pos = base + rank;
-      perm[pos] = i;
-      inv_pos[i] = pos;
+      if (cap > 0 && rank >= cap) {
+        inv_pos[i] = -1;               // beyond the expert's capacity: dropped
+      } else {
+        const int pos = base + rank;
+        perm[pos] = i;
+        inv_pos[i] = pos;
+      }
     }
   }
 }
@@ -344,11 +357,11 @@ int launch_route(const RouteArgs& a, hipStream_t s) {
   if (a.x_dtype == BTX_BF16) launch_tokens<bf16_t>(a, nblk, bc, bg, bp, s);
   else launch_tokens<float>(a, nblk, bc, bg, bp, s);
   BTX_LAUNCH_CHECK();
-  route_scan_kernel<<<1, kScanThreads, 0, s>>>(nblk, a.T, a.E, a.k, a.lb_mode, a.lb_alpha, bc, bg, bp, bb, a.counts,
-                                               a.offsets, a.gate_sum, a.prob_sum, a.lb_loss);
+  route_scan_kernel<<<1, kScanThreads, 0, s>>>(nblk, a.T, a.E, a.k, a.cap, a.lb_mode, a.lb_alpha, bc, bg, bp, bb,
+                                               a.counts, a.offsets, a.gate_sum, a.prob_sum, a.lb_loss, a.perm);
   BTX_LAUNCH_CHECK();
   route_scatter_kernel<<<ceil_div(nblk, kWavesPerBlock), kWavesPerBlock * kWave, 0, s>>>(
-      nblk, a.T, a.E, a.k, a.topk_idx, bb, a.offsets, a.perm, a.inv_pos);
+      nblk, a.T, a.E, a.k, a.cap, a.topk_idx, bb, a.offsets, a.perm, a.inv_pos);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }

@@ -34,8 +34,11 @@ __global__ __launch_bounds__(256) void router_ds_kernel(
   if (lane < k) {
     my_e = topk_idx[(size_t)t * k + lane];
     g = gates[(size_t)t * k + lane];
-    const float* part = dg_part + (size_t)inv_pos[(size_t)t * k + lane] * n_part;
-    for (int p = 0; p < n_part; ++p) dg += part[p];
+    const int r = inv_pos[(size_t)t * k + lane];
+    if (r >= 0) {                            // a dropped pair produced no output: dg = 0
+      const float* part = dg_part + (size_t)r * n_part;
+      for (int p = 0; p < n_part; ++p) dg += part[p];
+    }
   }
   if (flags & BTX_FLAG_LB_GRAD_THROUGH_U) {
     const float pb = __shfl(pbar, my_e < 0 ? 0 : my_e, kWave);
@@ -209,8 +212,10 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ d
       const int t = t0 + tq + q;
       if (t >= T) break;
       for (int j = 0; j < k; ++j) {
+        const int r = inv_pos[(size_t)t * k + j];
+        if (r < 0) continue;
         float v[8];
-        Ld8<XT>::ld(dxs + (size_t)inv_pos[(size_t)t * k + j] * d + c0, v);
+        Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[q][i] += v[i];
       }

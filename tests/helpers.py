@@ -56,13 +56,13 @@ def reconcile_routing(idx_gpu: np.ndarray, orc: dict, mode: int, U):
     return forced, len(diff)
 
 
-def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False, tau=1.0):
+def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False, tau=1.0, cf=0.0):
     return O.moe_forward(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
                          experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["U"]), alpha, lb_mode,
-                         forced_idx=forced, keep_y=keep_y, tau=tau)
+                         forced_idx=forced, keep_y=keep_y, tau=tau, capacity_factor=cf)
 
 
-def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True, tau=1.0):
+def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True, tau=1.0, cf=0.0):
     """Compare btx_moe_route's outputs with the oracle.  Returns the oracle's forward
     result (near-tie rows forced to the GPU's choice); with full_forward=False only the
     routing part and the statistics are evaluated (what full-size tests can afford)."""
@@ -70,23 +70,25 @@ def check_route(r: B.Routing, L, k, mode, alpha, lb_mode, full_forward=True, tau
     U = to_np(L["U"])
     x, Wr, b = to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"])
     idx_gpu = r.topk_idx.cpu().numpy().astype(np.int64)
-    orc = O.route(x, Wr, b, k, mode, U, tau=tau)
+    orc = O.route(x, Wr, b, k, mode, U, tau=tau, capacity_factor=cf)
     forced, n_forced = reconcile_routing(idx_gpu, orc, mode, U)
     assert n_forced <= max(1, idx_gpu.shape[0] // 1000), f"{n_forced} near-tie rows is implausibly many"
     if full_forward:
-        fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True, tau=tau)
+        fwd = run_oracle_forward(L, k, mode, alpha, lb_mode, forced if n_forced else None, keep_y=True, tau=tau, cf=cf)
     else:
-        fwd = O.route(x, Wr, b, k, mode, U, forced_idx=forced, tau=tau) if n_forced else orc
+        fwd = O.route(x, Wr, b, k, mode, U, forced_idx=forced, tau=tau, capacity_factor=cf) if n_forced else orc
         fwd.update(O.lb_statistics(fwd["idx"], fwd["gates"], fwd["probs"], alpha, lb_mode))
     fwd["n_forced"] = n_forced
     assert np.array_equal(fwd["idx"], idx_gpu)
     assert_close(r.gates.cpu().numpy(), fwd["gates"], ROUTER_TOL, "gates")
     assert_close(r.probs.cpu().numpy(), fwd["probs"], ROUTER_TOL, "probs")
     assert np.array_equal(r.counts.cpu().numpy(), fwd["counts"]), "counts"
-    grp = O.grouping(fwd["idx"], E)
+    grp = O.grouping(fwd["idx"], E, fwd["dropped"])
     fwd.update(grp)
     assert np.array_equal(r.offsets.cpu().numpy(), grp["offsets"]), "offsets"
-    assert np.array_equal(r.perm.cpu().numpy(), grp["perm"]), "perm"
+    n_kept = grp["perm"].size
+    assert np.array_equal(r.perm.cpu().numpy()[:n_kept], grp["perm"]), "perm"
+    assert not r.perm.cpu().numpy()[n_kept:].any(), "perm past the kept rows must be 0"
     assert np.array_equal(r.inv_pos.cpu().numpy(), grp["inv_pos"]), "inv_pos"
     assert_close(r.gate_sum.cpu().numpy(), fwd["gate_sum"], ROUTER_TOL, "gate_sum")
     assert_close(r.prob_sum.cpu().numpy(), fwd["prob_sum"], ROUTER_TOL, "prob_sum")
@@ -113,7 +115,7 @@ def router_condition(fwd, ref, mode) -> float:
 
 def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_mode=B.BTX_LB_TOKEN_FRAC, alpha=0.01,
                         lam=1.0, flags=0, bias=None, backward=True, seed=synth.BASE_SEED, unit_rms=False,
-                        dW_dtype=None, identical=False, split=1, expert_spread=0.1, check_router_grads=True, tau=1.0):
+                        dW_dtype=None, identical=False, split=1, expert_spread=0.1, check_router_grads=True, tau=1.0, cf=0.0):
     """One full route -> forward -> backward on the GPU, checked element by element."""
     n_seed = E // split
     L = synth.make_layer(T, d, f * split, n_seed, dtype=dtype, seed=seed, unit_rms=unit_rms, router_E=E,
@@ -129,8 +131,9 @@ def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
         for name in ("W1", "W3", "W2"):
             assert np.array_equal(to_np(G[name]), to_np(L[name])), "split re-indexing differs"
     tol = TOL[dtype]
-    r = B.btx_moe_route(G["x"], G["W_router"], G["b_router"], G["U"], k, mode, lb_mode, alpha, tau=tau)
-    fwd = check_route(r, L, k, mode, alpha, lb_mode, tau=tau)
+    r = B.btx_moe_route(G["x"], G["W_router"], G["b_router"], G["U"], k, mode, lb_mode, alpha, tau=tau,
+                        capacity_factor=cf)
+    fwd = check_route(r, L, k, mode, alpha, lb_mode, tau=tau, cf=cf)
     out, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, save=backward)
     assert_close(to_np(out), fwd["out"], tol, "out")
     if not backward:
@@ -152,7 +155,7 @@ def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
         got = to_np(getattr(g, name))
         for e in range(E):
             want = ref[name][e]
-            if want is None or fwd["counts"][e] == 0:
+            if want is None or fwd["offsets"][e + 1] == fwd["offsets"][e]:
                 assert not got[e].any(), f"{name}[{e}] must be zero for an expert without rows"
             else:
                 assert_close(got[e], want, tol, f"{name}[{e}]")

@@ -46,8 +46,8 @@ def test_route_rejects_bad_arguments(lib):
     p = ctypes.c_void_p(256)   # never dereferenced: validation fails first
     null = None
 
-    def route(T=8, d=64, E=4, k=2, mode=0, lb=0, U=null, x=p, ws_bytes=1 << 20, dtype=0, tau=1.0):
-        return lib.btx_moe_route(x, dtype, p, null, U, T, d, E, k, mode, lb, 0.0, tau, p, p, p, p, p, p, p, p, p, p, p,
+    def route(T=8, d=64, E=4, k=2, mode=0, lb=0, U=null, x=p, ws_bytes=1 << 20, dtype=0, tau=1.0, cf=0.0):
+        return lib.btx_moe_route(x, dtype, p, null, U, T, d, E, k, mode, lb, 0.0, tau, cf, p, p, p, p, p, p, p, p, p, p, p,
                                  ws_bytes, null)
 
     assert route(k=5) == 1                 # k > E
@@ -61,6 +61,7 @@ def test_route_rejects_bad_arguments(lib):
     assert route(mode=2, k=1) == 1         # sampling needs U
     assert route(mode=0, U=p) == 1         # U only with sampling
     assert route(lb=2) == 1
+    assert route(cf=-0.5) == 1             # capacity factor: 0 (none) or positive
     assert route(dtype=7) == 1
     assert route(x=null) == 1
     assert route(ws_bytes=16) == 3         # workspace too small

@@ -65,6 +65,23 @@ def test_gumbel_without_noise_at_unit_temperature_is_switch_routing():
     assert_close(a.gates.cpu().numpy(), b.gates.cpu().numpy().astype(np.float64), 1e-6, "gates")
 
 
+@pytest.mark.parametrize("mode,k,cf,bias", [(B.BTX_ROUTE_SWITCH_TOP1, 1, 1.5, [2.0, 0, 0, 0]),
+                                            (B.BTX_ROUTE_SWITCH_TOP1, 1, 0.5, None),
+                                            (B.BTX_ROUTE_TOPK_RENORM, 2, 0.75, [1.0, 0, 0, -1.0]),
+                                            (B.BTX_ROUTE_TOPK_RENORM, 2, 4.0, None)])
+def test_capacity_factor_drops_pairs_in_token_order_fp32(mode, k, cf, bias):
+    G, r, out, g = run_layer_and_check(301, 72, 88, 4, k, F32, mode=mode, bias=bias, cf=cf)
+    dropped = int((r.inv_pos < 0).sum())
+    assert (dropped > 0) == (cf < 4.0)
+    assert int(r.offsets[-1]) == 301 * k - dropped
+
+
+def test_capacity_factor_gate_mean_statistics_fp32():
+    # (capacity factors in these tests are exact in binary: the C ABI takes a float)
+    run_layer_and_check(257, 64, 64, 4, 2, F32, lb_mode=B.BTX_LB_GATE_MEAN, flags=B.BTX_FLAG_LB_GRAD_THROUGH_U,
+                        bias=[1.5, 0, 0, 0], cf=0.625)
+
+
 def test_expert_without_tokens_fp32():
     """A strongly negative bias starves expert 2: empty group, zero weight gradients."""
     G, r, out, g = run_layer_and_check(300, 64, 80, 4, 2, F32, bias=[0, 0, -60.0, 0])
@@ -154,6 +171,17 @@ def test_bf16_sample_top1_imbalanced():
 
 def test_bf16_gumbel_sample_top1():
     run_layer_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_GUMBEL_TOP1, unit_rms=True, tau=0.5)
+
+
+def test_bf16_switch_with_capacity_factor():
+    """Switch routing at capacity factor 1.5 with a router that overloads expert 0 (Sec. 4.3)."""
+    G, r, out, g = run_layer_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_SWITCH_TOP1, bias=[2.0, 0, 0, 0],
+                                       unit_rms=True, cf=1.5)
+    assert int((r.inv_pos < 0).sum()) > 0 and int(r.offsets[1]) == 338   # ceil(1.5 * 900 / 4)
+
+
+def test_bf16_top2_with_capacity_factor():
+    run_layer_and_check(1500, 512, 1376, 8, 4, BF16, unit_rms=True, cf=0.75, bias=[1.0, 0.5, 0, 0, 0, 0, -0.5, -1.0])
 
 
 def test_bf16_expert_without_tokens():
