@@ -32,12 +32,6 @@
 #define BTX_SUP_N 16
 #define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
 #endif
-#ifndef BTX_DEV
-#define BTX_DEV 0      // dev only: timing experiments
-#endif
-#ifndef BTX_TIMERS
-#define BTX_TIMERS 0   // dev only: per-phase cycle counters written to MArgs::dg_part
-#endif
 
 namespace btx {
 namespace {
@@ -60,9 +54,6 @@ struct MArgs {
   int c_is_f32;
   int sup_m, sup_n, xcd_m;             // supertile shape in tiles, XCDs along its rows
   int blocks_per_e;                     // grouped-K: block ids per expert (a multiple of 8)
-#if BTX_DEV
-  int dev_flags, dev_delay;
-#endif
 };
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -228,12 +219,6 @@ struct Gemm {
       }
     }
 
-#if BTX_DEV
-    if ((g.dev_flags & 2) && blockIdx.x < 256) {
-      const int slot8 = (g.dev_flags & 4) ? (blockIdx.x / 8) % 8 : blockIdx.x % 8;
-      for (int w = 0; w < slot8 * g.dev_delay; ++w) __builtin_amdgcn_s_sleep(127);
-    }
-#endif
     int row0, row_end, k_begin, k_end;
     int kp_begin = 0;                                   // first padded row of expert e (transposed operand)
     if (GROUP_K) {
@@ -385,8 +370,6 @@ struct Gemm {
       constexpr int HS = KSTEPS / 2;                 // k steps per half tile
       const int grp = wave / (NW / 2);               // group 1 lags group 0 by one phase
       bf16x8 fa[HS][TM], fb[HS][TN];
-      unsigned long long tm = 0, tb1 = 0, tc = 0, tv = 0, tb2 = 0;
-      auto now = [&]() -> unsigned long long { return BTX_TIMERS ? __builtin_readcyclecounter() : 0ull; };
       if (nk > 0) {
         issueA(0);
         issueB(0);
@@ -399,35 +382,23 @@ struct Gemm {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           // ---- memory phase
-          const unsigned long long t0 = now();
 #pragma unroll
           for (int x = 0; x < HS; ++x) load_frags(kt, h * HS + x, fa[x], fb[x]);
           if (h == 0 && kt + 1 < nk) issueB(kt + 1);
           if (h == 1 && kt + 2 < nk) issueA(kt + 2);
           __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): fragments are in registers
-          const unsigned long long t1 = now();
           if (h == 1 && grp == 1) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
-          const unsigned long long t2 = now();
           __builtin_amdgcn_sched_barrier(0);
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          const unsigned long long t3 = now();
           // ---- compute phase
 #pragma unroll
           for (int x = 0; x < HS; ++x) mfma_step(fa[x], fb[x]);
-          const unsigned long long t4 = now();
           if (h == 1 && grp == 0) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
-          const unsigned long long t5 = now();
           __builtin_amdgcn_sched_barrier(0);
           if (!(grp == 1 && h == 1 && kt + 1 == nk)) __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
-          const unsigned long long t6 = now();
-          tm += t1 - t0; tv += (t2 - t1) + (t5 - t4); tb1 += t3 - t2; tc += t4 - t3; tb2 += t6 - t5;
         }
-      }
-      if (BTX_TIMERS && lane == 0 && g.dg_part) {
-        float* o = g.dg_part + ((size_t)blockIdx.x * NW + wave) * 8;
-        o[0] = (float)tm; o[1] = (float)tb1; o[2] = (float)tc; o[3] = (float)tb2; o[4] = (float)tv; o[5] = (float)nk;
       }
     } else {
       // Plain NSTAGE-deep pipeline, one barrier per tile.  The loop is rotated by one k step:
@@ -468,9 +439,6 @@ struct Gemm {
       }
     }
 
-#if BTX_DEV
-    if (g.dev_flags & 1) return;
-#endif
     // ---- epilogue ----------------------------------------------------------
     // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
     //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
