@@ -119,11 +119,13 @@ def dropped_pairs(idx: np.ndarray, E: int, cap: int) -> np.ndarray:
 
 
 def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau: float = 1.0,
-          capacity_factor: float = 0.0) -> Dict[str, np.ndarray]:
+          capacity_factor: float = 0.0, forced_dropped=None) -> Dict[str, np.ndarray]:
     """Logits, full softmax, chosen experts idx[T,k] and their gates[T,k].
 
     forced_idx[T,k] (entries < 0 = not forced) overrides the selection of
     individual tokens; the gate formulas are then applied to the forced set.
+    forced_dropped[T,k] replaces the capacity decision (for evaluating a sample of
+    a batch whose drops were decided on the whole batch).
 
     ROUTE_GUMBEL_TOP1 (Sec. 3.3 "Sample Top-1", training time): U is the Gumbel
     noise G[T,E] drawn by the caller and tau the temperature; the soft sample is
@@ -175,7 +177,8 @@ def route(x, W_router, b_router, k: int, mode: int, U=None, forced_idx=None, tau
     else:
         gates = np.take_along_axis(p, idx, axis=1)
     res = {"logits": s, "probs": p, "idx": idx, "gates": gates,
-           "dropped": dropped_pairs(idx, E, capacity(T, k, E, capacity_factor))}
+           "dropped": (np.asarray(forced_dropped, dtype=bool) if forced_dropped is not None
+                       else dropped_pairs(idx, E, capacity(T, k, E, capacity_factor)))}
     if gate_probs is not None:
         res["gate_probs"] = gate_probs
     return res
@@ -236,7 +239,8 @@ def grouping(idx: np.ndarray, E: int, dropped: Optional[np.ndarray] = None) -> D
 # --------------------------------------------------------------------------
 def moe_forward(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOPK_RENORM, U=None,
                 alpha: float = 0.0, lb_mode: int = LB_TOKEN_FRAC, forced_idx=None,
-                keep_y: bool = False, tau: float = 1.0, capacity_factor: float = 0.0) -> Dict[str, np.ndarray]:
+                keep_y: bool = False, tau: float = 1.0, capacity_factor: float = 0.0,
+                forced_dropped=None) -> Dict[str, np.ndarray]:
     """out_t = sum_i g_i(W_l x_t) FF_i(x_t), evaluating FF_i only where the
     gate is non-zero (the paper's own remark that zero-gate experts are
     skipped); W1/W3/W2 are sequences of per-expert matrices.  With a capacity
@@ -244,7 +248,7 @@ def moe_forward(x, W_router, b_router, W1, W3, W2, k: int, mode: int = ROUTE_TOP
     x = np.asarray(x, F64)
     T, d = x.shape
     E = len(W1)
-    r = route(x, W_router, b_router, k, mode, U, forced_idx, tau, capacity_factor)
+    r = route(x, W_router, b_router, k, mode, U, forced_idx, tau, capacity_factor, forced_dropped)
     idx, gates = r["idx"], r["gates"]
     kept = ~r["dropped"]
     out = np.zeros((T, d), dtype=F64)

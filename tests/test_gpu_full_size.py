@@ -37,7 +37,8 @@ def f32(t):
 
 
 def sample_tokens(fwd, k, n_random, rng):
-    """Tokens owning the first/last grouped row of each expert, rows around tile edges, and random ones."""
+    """Tokens owning the first/last grouped row of each expert, rows around tile edges, random ones,
+    and (with a capacity limit) the last kept and the first dropped pair of every expert."""
     perm, offsets = fwd["perm"], fwd["offsets"]
     rows = set()
     for e in range(len(offsets) - 1):
@@ -47,19 +48,25 @@ def sample_tokens(fwd, k, n_random, rng):
             for edge in range(a + 256, b, 256 * 7):
                 rows.update([edge - 1, edge])
     toks = {int(perm[r]) // k for r in rows}
+    if fwd["dropped"].any():
+        for e in range(len(offsets) - 1):
+            tt, jj = np.nonzero((fwd["idx"] == e) & fwd["dropped"])
+            if tt.size:
+                toks.update([int(tt[0]), int(tt[-1])])
     toks.update(int(t) for t in rng.integers(0, fwd["idx"].shape[0], n_random))
     return np.array(sorted(toks))
 
 
-def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True, n_random=24, n_cols=6, seed=0):
+def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True, n_random=24, n_cols=6, seed=0,
+             noise=None, tau=1.0, cf=0.0):
     rng = np.random.default_rng(seed)
     E, d, f = W1.shape[0], W1.shape[1], W1.shape[2]
     x, dY = L["x"][:T].contiguous(), L["dY"][:T].contiguous()
-    U = L["U"][:T].contiguous() if mode == B.BTX_ROUTE_SAMPLE_TOP1 else None
+    U = L["U"][:T].contiguous() if mode == B.BTX_ROUTE_SAMPLE_TOP1 else noise
     b = None if bias is None else torch.tensor(bias, dtype=torch.float32, device=x.device)
-    r = B.btx_moe_route(x, Wr, b, U, k, mode, B.BTX_LB_TOKEN_FRAC, alpha)
+    r = B.btx_moe_route(x, Wr, b, U, k, mode, B.BTX_LB_TOKEN_FRAC, alpha, tau=tau, capacity_factor=cf)
     Lr = {"x": x, "W_router": Wr, "b_router": b, "U": U}
-    fwd = check_route(r, Lr, k, mode, alpha, B.BTX_LB_TOKEN_FRAC, full_forward=False)
+    fwd = check_route(r, Lr, k, mode, alpha, B.BTX_LB_TOKEN_FRAC, full_forward=False, tau=tau, cf=cf)
     out, h1, h3 = B.btx_moe_ff_forward(x, W1, W3, W2, r, save=backward)
 
     toks = sample_tokens(fwd, k, n_random, rng)
@@ -69,20 +76,21 @@ def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True
     W2n = [f32(W2[e]) for e in range(E)]
     forced = fwd["idx"][toks]          # the sample follows the reconciled full-batch routing
     sub = O.moe_forward(xs_np, Wr_np, b_np, W1n, W3n, W2n, k, mode, None if U is None else f32(U[toks]),
-                        forced_idx=forced)
+                        forced_idx=forced, tau=tau, forced_dropped=fwd["dropped"][toks])
     assert_close(f32(out[toks]), sub["out"], TOL[BF16], "out[sample]")
     if not backward:
         return r, out, None, fwd
 
-    g = B.btx_moe_ff_backward(dY, x, Wr, W1, W3, W2, r, h1, h3, mode, B.BTX_LB_TOKEN_FRAC, alpha, lam)
+    g = B.btx_moe_ff_backward(dY, x, Wr, W1, W3, W2, r, h1, h3, mode, B.BTX_LB_TOKEN_FRAC, alpha, lam,
+                              noise=noise if mode == B.BTX_ROUTE_GUMBEL_TOP1 else None, tau=tau)
     ref = O.moe_backward(xs_np, Wr_np, b_np, W1n, W3n, W2n, k, mode, f32(dY[toks]), sub, alpha, O.LB_TOKEN_FRAC, lam,
-                         batch_stats={"u": fwd["u"], "pbar": fwd["pbar"], "T": T}, want_dW=False)
+                         batch_stats={"u": fwd["u"], "pbar": fwd["pbar"], "T": T}, want_dW=False, tau=tau)
     assert_close(f32(g.dX[toks]), ref["dX"], TOL[BF16], "dX[sample]")
 
     # weight gradients: a few d_ff indices per expert, over all of that expert's tokens
     x_all, dY_all = f32(x), f32(dY)
     for e in range(E):
-        tt, jj = np.nonzero(fwd["idx"] == e)
+        tt, jj = np.nonzero((fwd["idx"] == e) & ~fwd["dropped"])
         cols = np.unique(np.concatenate([[0, f - 1], rng.integers(0, f, n_cols)]))
         if tt.size == 0:
             assert not f32(g.dW1[e]).any() and not f32(g.dW2[e]).any()
@@ -117,6 +125,27 @@ def test_config2_forward_backward_T16384_as_benchmarked(big):
                                lb_grad_scale=1.0)
     for a, b in ((out, out2), (g.dX, g2.dX), (g.dW1, g2.dW1), (g.dW2, g2.dW2), (g.dW_router, g2.dW_router)):
         assert torch.equal(a, b)
+
+
+def test_config3_gumbel_sample_top1(big):
+    """Sample top-1 as printed (Gumbel-softmax soft sample, largest entry kept), temperature 0.5."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(synth.BASE_SEED + 77)
+    u = torch.rand((T_FULL, 4), generator=g, device="cuda", dtype=torch.float32).clamp_(1e-7, 1 - 1e-7)
+    noise = -torch.log(-torch.log(u))
+    run_full(big, T_FULL, 1, B.BTX_ROUTE_GUMBEL_TOP1, 0.01, 1.0, big["W1"], big["W3"], big["W2"], big["W_router"],
+             noise=noise, tau=0.5)
+
+
+def test_config3_switch_with_capacity_factor(big):
+    """Switch routing at the capacity factor of Sec. 4.3 (1.5) with a router that overloads expert 0:
+    it keeps ceil(1.5 * T / 4) = 6144 tokens and the rest of its tokens pass through with no FF output."""
+    r, out, g, fwd = run_full(big, T_FULL, 1, B.BTX_ROUTE_SWITCH_TOP1, 0.01, 1.0, big["W1"], big["W3"], big["W2"],
+                              big["W_router"], bias=[2.0, 0.0, 0.0, 0.0], cf=1.5)
+    assert int(r.offsets[1]) == 6144 and fwd["counts"][0] > 6144
+    dropped = (r.inv_pos[:, 0] < 0)
+    assert int(dropped.sum()) == fwd["counts"][0] - 6144
+    assert not out[dropped].any()          # no expert ran for these tokens
 
 
 @pytest.mark.parametrize("mode", [B.BTX_ROUTE_SWITCH_TOP1, B.BTX_ROUTE_SAMPLE_TOP1])

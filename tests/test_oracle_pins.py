@@ -352,6 +352,10 @@ def test_capacity_keeps_the_first_pairs_of_every_expert():
     dense = O.dense_gates(r["idx"], np.where(r["dropped"], 0.0, r["gates"]), 3)
     want = sum(dense[:, e:e + 1] * O.expert_ff(x, W1[e], W3[e], W2[e]) for e in range(3))
     np.testing.assert_allclose(f["out"], want, rtol=1e-12, atol=1e-14)
+    # a sample of the batch evaluated with the whole batch's drop decisions gives the same rows
+    sel = np.array([1, 4, 8])
+    sub = O.moe_forward(x[sel], Wr, None, W1, W3, W2, 2, forced_idx=r["idx"][sel], forced_dropped=r["dropped"][sel])
+    np.testing.assert_allclose(sub["out"], f["out"][sel], rtol=1e-12, atol=1e-14)
     # a limit nobody reaches
     a = O.moe_forward(x, Wr, None, W1, W3, W2, 2, capacity_factor=3.0)
     z = O.moe_forward(x, Wr, None, W1, W3, W2, 2)
