@@ -33,6 +33,13 @@ WORKLOAD = dict(name="llama2-7b-shaped MoE-FF layer, fwd+bwd, T=16384 (4 seq x 4
 # FETCH_SIZE / WRITE_SIZE read this fraction of the known traffic of a plain streaming kernel (combine_kernel;
 # see profiles/layer_fwd_bwd_c2_pmc_counters.txt): 128-byte reads are counted as 64 bytes on this chip
 FETCH_FACTOR, WRITE_FACTOR = 0.5027, 1.000
+# routing variants that can be timed; top2 is the benchmark configuration
+VARIANTS = {
+    "top2": dict(name="top-2", k=2, mode=0, bias=None, tau=1.0, cf=0.0),
+    "switch-cf1.5": dict(name="Switch top-1, router bias +2 on expert 0, capacity factor 1.5", k=1, mode=1,
+                         bias=[2.0, 0.0, 0.0, 0.0], tau=1.0, cf=1.5),
+    "gumbel": dict(name="Gumbel-softmax sample top-1, tau 0.5", k=1, mode=3, bias=None, tau=0.5, cf=0.0),
+}
 GEMM_STAGES = {"up_swiglu": 4, "down": 2, "bwd_act": 2, "bwd_dx": 4, "dw13": 4, "dw2": 2}   # x d*f*R flops
 
 
@@ -140,6 +147,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--tokens", type=int, default=WORKLOAD["T"], help="override T (parity/dev runs only)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--variant", default="top2", choices=sorted(VARIANTS),
+                    help="routing variant; only top2 is the benchmark of record, the others are extra measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -147,10 +156,14 @@ def main():
 
     W = dict(WORKLOAD)
     W["T"] = args.tokens
+    V = VARIANTS[args.variant]
+    W["k"] = V["k"]
     T, d, f, E, k, alpha = W["T"], W["d"], W["f"], W["E"], W["k"], W["alpha"]
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    L = synth.make_layer(T, d, f, E, dtype=torch.bfloat16, device=dev, unit_rms=True, with_dY=True)
+    L = synth.make_layer(T, d, f, E, dtype=torch.bfloat16, device=dev, unit_rms=True, with_dY=True,
+                         router_bias=V["bias"], with_gumbel=V["mode"] == B.BTX_ROUTE_GUMBEL_TOP1)
+    noise = L["U"] if V["mode"] == B.BTX_ROUTE_GUMBEL_TOP1 else None
     lib = B.load_library()
 
     # everything a step writes is allocated once, outside the timed region
@@ -167,11 +180,12 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def step():
-        B.btx_moe_route(L["x"], L["W_router"], None, None, k, B.BTX_ROUTE_TOPK_RENORM, B.BTX_LB_TOKEN_FRAC, alpha,
-                        out=routing, workspace=ws)
+        B.btx_moe_route(L["x"], L["W_router"], L["b_router"], noise, k, V["mode"], B.BTX_LB_TOKEN_FRAC, alpha,
+                        out=routing, workspace=ws, tau=V["tau"], capacity_factor=V["cf"])
         B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, save=True, out=out, saved=saved, workspace=ws)
         B.btx_moe_ff_backward(L["dY"], L["x"], L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
-                              B.BTX_ROUTE_TOPK_RENORM, B.BTX_LB_TOKEN_FRAC, alpha, 1.0, 0, out=grads, workspace=ws)
+                              V["mode"], B.BTX_LB_TOKEN_FRAC, alpha, 1.0, 0, out=grads, workspace=ws, noise=noise,
+                              tau=V["tau"])
 
     for _ in range(args.warmup):
         step()
@@ -196,7 +210,7 @@ def main():
     for i, name in enumerate(B.STAGE_NAMES):
         v = [events.elapsed_ms(2 * n_stage * s + 2 * i, 2 * n_stage * s + 2 * i + 1) for s in range(args.steps)]
         stage_ms[name] = float(np.mean(v))
-    R = T * k
+    R = int(routing.offsets[-1].item())     # grouped rows the expert GEMMs worked on (T*k unless pairs were dropped)
     gemm = {n: {"ms": stage_ms[n], "tflops": c * d * f * R / (stage_ms[n] * 1e-3) / 1e12} for n, c in GEMM_STAGES.items()}
     dominant = max(gemm, key=lambda n: gemm[n]["ms"])
     gemm_ms = sum(v["ms"] for v in gemm.values())
@@ -209,11 +223,12 @@ def main():
         "value": T * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": W["name"] if T == WORKLOAD["T"] else f"dev run, T={T}", "tokens": T, "d_model": d,
+        "config": {"workload": (W["name"] if args.variant == "top2" else W["name"].replace("top-2", V["name"]))
+                   if T == WORKLOAD["T"] else f"dev run, T={T}, {V['name']}", "tokens": T, "routed_rows": R, "d_model": d,
                    "d_ff": f, "experts": E, "top_k": k},
         "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm[dominant]["tflops"] / PEAK_BF16_TFLOPS,
-                     "traffic": profiled_traffic(dominant) if T == WORKLOAD["T"] else None,
+                     "traffic": profiled_traffic(dominant) if T == WORKLOAD["T"] and args.variant == "top2" else None,
                      "algorithmic_flops": GEMM_STAGES[dominant] * d * f * R,
                      # register-fed MFMA loop on the same x: the ceiling at the clock the chip sustains
                      "sustained_mfma_peak": sustained, "frac_of_sustained": gemm[dominant]["tflops"] / sustained},
@@ -225,7 +240,7 @@ def main():
         "step_ms": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},
         "hbm_stages": hbm_stages(stage_ms, T, d, E, k),
     }
-    if args.cpu_sample > 0:
+    if args.cpu_sample > 0 and args.variant == "top2":   # the oracle is timed on the benchmark configuration only
         result["cpu_baseline"] = cpu_baseline(L, W, min(args.cpu_sample, T))
     print(json.dumps(result))
 
