@@ -432,6 +432,22 @@ def merge_average(tensors: Sequence[np.ndarray]) -> np.ndarray:
     return acc / len(tensors)
 
 
+def adamw_step(p, g, m, v, step: int, lr: float, beta1: float, beta2: float, eps: float, weight_decay: float):
+    """One AdamW update (Sec. 4.1 names the optimizer and its weight decay, 0.1; the moment
+    decay rates and eps are inputs): decoupled weight decay, bias-corrected moments,
+        m <- b1 m + (1-b1) g,  v <- b2 v + (1-b2) g^2,
+        p <- p - lr * ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd * p ),   t = step >= 1.
+    Returns the new (p, m, v) in float64."""
+    p, g, m, v = (np.asarray(a, F64) for a in (p, g, m, v))
+    assert step >= 1
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    p = p - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * p)
+    return p, m, v
+
+
 def round_to_bf16(v: np.ndarray) -> np.ndarray:
     """Round float64 values to the nearest bfloat16 (ties to even), returned as
     float32.  One rounding, straight from float64.  Values are assumed finite

@@ -473,6 +473,33 @@ def test_blend_deals_hidden_units_out_without_changing_their_sum():
         np.testing.assert_array_equal(b2[n], np.concatenate([s2[i * 3 + n] for i in range(3)], axis=0))
 
 
+def test_adamw_step_closed_forms_and_library_routine():
+    """Pins of the AdamW update: the first step moves every weight by lr*(sign(g) + wd*p) when
+    eps is negligible; a zero gradient leaves pure decay; and a sequence of steps follows
+    torch.optim.AdamW (decoupled decay, bias correction) in float64."""
+    rng = np.random.default_rng(9)
+    p = rng.normal(size=(5, 7))
+    g = rng.normal(size=(5, 7))
+    z = np.zeros_like(p)
+    p1, m1, v1 = O.adamw_step(p, g, z, z, 1, 1e-2, 0.9, 0.95, 1e-30, 0.1)
+    np.testing.assert_allclose(p1, p - 1e-2 * (np.sign(g) + 0.1 * p), rtol=1e-12)
+    np.testing.assert_allclose(m1, 0.1 * g, rtol=1e-13)
+    np.testing.assert_allclose(v1, 0.05 * g * g, rtol=1e-13)
+    p0, m0, v0 = O.adamw_step(p, z, z, z, 1, 1e-2, 0.9, 0.95, 1e-8, 0.1)
+    np.testing.assert_allclose(p0, p * (1 - 1e-3), rtol=1e-13)
+    assert not m0.any() and not v0.any()
+    import torch
+    tp = torch.tensor(p, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([tp], lr=3e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=0.1)
+    po, mo, vo = p, z, z
+    for step in range(1, 6):
+        gs = rng.normal(size=p.shape)
+        tp.grad = torch.tensor(gs, dtype=torch.float64)
+        opt.step()
+        po, mo, vo = O.adamw_step(po, gs, mo, vo, step, 3e-3, 0.9, 0.95, 1e-8, 0.1)
+        np.testing.assert_allclose(po, tp.detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
 def test_merge_average():
     a = RNG.normal(size=(5, 7)).astype(np.float32)
     for n in (1, 2, 3, 4, 7):
