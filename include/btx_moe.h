@@ -244,6 +244,23 @@ typedef enum { BTX_MIX_SPLIT = 0, BTX_MIX_BLEND = 1 } btx_mix_mode;
 int btx_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
                     void* oW1, void* oW3, void* oW2, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * btx_adamw_step - fused AdamW update (Sec. 4.1: "AdamW optimizer with weight decay
+ * 0.1"; the moment decay rates and eps are not stated and are arguments), for the
+ * weight gradients btx_moe_ff_backward returns:
+ *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2
+ *   p <- p - lr * ( (m/(1-beta1^step)) / (sqrt(v/(1-beta2^step)) + eps) + weight_decay * p )
+ * in fp32, elementwise, in place.
+ *   master, m, v  DEVICE [numel] fp32, 16-byte aligned: master weights and moments
+ *   grad          DEVICE [numel] grad_dtype (BTX_BF16 or BTX_F32), 16-byte aligned
+ *   lowp          DEVICE [numel] bf16, 8-byte aligned, may be NULL: receives the updated
+ *                 weights rounded once to bf16 (the copy the layer's GEMMs read)
+ *   step          1-based count of updates, for the bias corrections
+ * Errors: BTX_ERR_INVALID_ARG (NULL / misaligned pointers, step < 1, beta outside [0,1),
+ * negative eps), BTX_ERR_HIP. */
+int btx_adamw_step(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, int64_t numel,
+                   int step, float lr, float beta1, float beta2, float eps, float weight_decay, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -40,6 +40,7 @@ _SIGNATURES = {
     "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u, _vp, _f] + [_vp] * 11 + [_vp] * 6 +
                             [_i, _vp, _sz, _vp]),
     "btx_merge_average": (_i, [ctypes.POINTER(_vp), _i, _vp, _i64, _i, _vp]),
+    "btx_adamw_step": (_i, [_vp, _vp, _vp, _vp, _i, _vp, _i64, _i, _f, _f, _f, _f, _f, _vp]),
     "btx_mix_experts": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
 }
 
@@ -231,6 +232,18 @@ def btx_probe_mfma(data: torch.Tensor, n_blocks: int = 256, iters: int = 1000) -
                             ctypes.byref(flops), _stream())
     _check(st, "btx_probe_mfma")
     return flops.value
+
+
+def btx_adamw_step(master: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grad: torch.Tensor, step: int, lr: float,
+                   beta1: float = 0.9, beta2: float = 0.95, eps: float = 1e-8, weight_decay: float = 0.1,
+                   lowp: Optional[torch.Tensor] = None) -> None:
+    """In-place fused AdamW on fp32 master weights and moments; lowp (bf16) receives the rounded weights."""
+    lib = load_library()
+    assert master.dtype == m.dtype == v.dtype == torch.float32 and master.numel() == m.numel() == v.numel() == grad.numel()
+    assert lowp is None or (lowp.dtype == torch.bfloat16 and lowp.numel() == master.numel())
+    st = lib.btx_adamw_step(_ptr(master), _ptr(m), _ptr(v), _ptr(grad), _dtype_code(grad), _ptr(lowp), master.numel(),
+                            step, lr, beta1, beta2, eps, weight_decay, _stream())
+    _check(st, "btx_adamw_step")
 
 
 BTX_MIX_SPLIT, BTX_MIX_BLEND = 0, 1

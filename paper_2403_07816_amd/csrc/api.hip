@@ -242,6 +242,18 @@ int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel
   return launch_merge_average(inputs, N, out, numel, dtype, static_cast<hipStream_t>(stream));
 }
 
+int btx_adamw_step(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, int64_t numel,
+                   int step, float lr, float beta1, float beta2, float eps, float weight_decay, void* stream) {
+  if (!dtype_ok(grad_dtype) || numel < 0 || step < 1) return BTX_ERR_INVALID_ARG;
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f)) return BTX_ERR_INVALID_ARG;
+  if (numel == 0) return BTX_OK;
+  if (!master || !m || !v || !grad) return BTX_ERR_INVALID_ARG;
+  if ((((uintptr_t)master | (uintptr_t)m | (uintptr_t)v | (uintptr_t)grad) & 15) || ((uintptr_t)lowp & 7))
+    return BTX_ERR_INVALID_ARG;
+  return launch_adamw(master, m, v, grad, grad_dtype, lowp, numel, step, lr, beta1, beta2, eps, weight_decay,
+                      static_cast<hipStream_t>(stream));
+}
+
 int btx_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
                     void* oW1, void* oW3, void* oW2, void* stream) {
   if (!dtype_ok(dtype) || N < 1 || d < 1 || f < 1) return BTX_ERR_INVALID_ARG;

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <cmath>
+
 #include "btx_moe.h"
 
 namespace btx {
@@ -148,6 +151,8 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s);
 
 int launch_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, int N, int d, int f, int mode, int C,
                        void* oW1, void* oW3, void* oW2, hipStream_t s);
+int launch_adamw(float* P, float* M, float* V, const void* G, int grad_dtype, void* lowp, int64_t n, int step, float lr,
+                 float beta1, float beta2, float eps, float wd, hipStream_t s);
 int launch_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, hipStream_t s);
 
 }  // namespace btx

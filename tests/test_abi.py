@@ -121,6 +121,25 @@ def test_mix_experts_rejects_bad_arguments(lib):
     assert lib.btx_mix_experts(a, b, c, 7, 4, 64, 96, 0, 3, *ok_tail) == bad      # dtype
 
 
+def test_adamw_rejects_bad_arguments(lib):
+    bad = 1
+    a, b, c, g = (ctypes.c_void_p(0x1000 * i) for i in range(1, 5))
+
+    def step(master=a, grad=g, n=64, t=1, b1=0.9, b2=0.95, eps=1e-8, gdt=1, lowp=None):
+        return lib.btx_adamw_step(master, b, c, grad, gdt, lowp, n, t, 1e-4, b1, b2, eps, 0.1, None)
+
+    assert step(t=0) == bad
+    assert step(b1=1.0) == bad
+    assert step(b2=-0.1) == bad
+    assert step(eps=-1.0) == bad
+    assert step(master=None) == bad
+    assert step(grad=ctypes.c_void_p(0x4008)) == bad      # misaligned
+    assert step(lowp=ctypes.c_void_p(0x5004)) == bad
+    assert step(gdt=5) == bad
+    assert step(n=-1) == bad
+    assert step(n=0) == 0
+
+
 def test_probe_rejects_bad_arguments(lib):
     bad = 1  # BTX_ERR_INVALID_ARG
     dummy = ctypes.c_void_p(0x1000)

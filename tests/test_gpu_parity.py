@@ -244,6 +244,30 @@ def test_split_and_blend_match_the_oracle_bit_for_bit(dtype, N, d, f, C):
     assert torch.equal(b1, W1) and torch.equal(b3, W3) and torch.equal(b2, W2)
 
 
+# -------------------------------------------------------------------- AdamW
+@pytest.mark.parametrize("gdtype", [F32, BF16])
+@pytest.mark.parametrize("n", [4096 * 33 + 3, 5, 1 << 20])
+def test_adamw_steps_follow_the_oracle(gdtype, n):
+    g = torch.Generator().manual_seed(n)
+    p = torch.randn(n, generator=g) * 0.02
+    m = torch.zeros(n)
+    v = torch.zeros(n)
+    P, M, V = p.cuda(), m.cuda(), v.cuda()
+    low = torch.empty(n, dtype=BF16, device="cuda")
+    po, mo, vo = p.double().numpy(), m.double().numpy(), v.double().numpy()
+    for step in range(1, 4):
+        grad = (torch.randn(n, generator=g) * 1e-3).to(gdtype)
+        B.btx_adamw_step(P, M, V, grad.cuda(), step, 1e-4, 0.9, 0.95, 1e-8, 0.1, lowp=low)
+        po, mo, vo = O.adamw_step(po, grad.double().numpy(), mo, vo, step, 1e-4, 0.9, 0.95, 1e-8, 0.1)
+    # the update itself (weights move by ~1e-4 per step): compared as a difference from the start
+    start = p.double().numpy()
+    assert_close(P.cpu().double().numpy() - start, po - start, 1e-4, "update")
+    assert_close(M.cpu().numpy(), mo, 1e-5, "m")
+    assert_close(V.cpu().numpy(), vo, 1e-5, "v")
+    # working copy: the fp32 result rounded once
+    assert torch.equal(low, P.to(BF16))
+
+
 # ------------------------------------------------------------ measurement aid
 def test_mfma_probe_runs_and_counts_its_flops():
     data = torch.randn(1 << 20, device="cuda").to(torch.bfloat16)
