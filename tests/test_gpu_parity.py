@@ -244,6 +244,49 @@ def test_split_and_blend_match_the_oracle_bit_for_bit(dtype, N, d, f, C):
     assert torch.equal(b1, W1) and torch.equal(b3, W3) and torch.equal(b2, W2)
 
 
+def test_layer_step_replays_from_a_hip_graph():
+    """The three entry points only enqueue kernels on the given stream (no allocation, no
+    synchronisation, no memset nodes), so a whole step can be captured once and replayed.
+    Every replay, with eager work in between, must reproduce the eager results bit for bit."""
+    T, d, f, E, k = 700, 256, 384, 4, 2
+    L = to_dev(synth.make_layer(T, d, f, E, dtype=BF16, unit_rms=True, with_dY=True))
+    lib = B.load_library()
+    routing = B.alloc_routing(T, E, k, "cuda")
+    out = torch.empty_like(L["x"])
+    saved = (torch.empty((T * k, f), dtype=BF16, device="cuda"), torch.empty((T * k, f), dtype=BF16, device="cuda"))
+    grads = B.Grads(torch.empty_like(L["x"]), torch.empty((d, E), device="cuda"), torch.empty(E, device="cuda"),
+                    torch.empty_like(L["W1"]), torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
+    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, E, k),
+                         lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
+                         lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16)), dtype=torch.uint8,
+                     device="cuda")
+
+    def step():
+        B.btx_moe_route(L["x"], L["W_router"], None, None, k, lb_alpha=0.01, out=routing, workspace=ws)
+        B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, out=out, saved=saved, workspace=ws)
+        B.btx_moe_ff_backward(L["dY"], L["x"], L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
+                              lb_alpha=0.01, lb_grad_scale=1.0, out=grads, workspace=ws)
+
+    step()                                   # eager reference (also sets the kernels' LDS attributes)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (out, grads.dX, grads.dW_router, grads.dW1, grads.dW2, routing.perm)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        for t in (out, grads.dX, grads.dW_router, grads.dW1, grads.dW2):
+            t.zero_()                        # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((out, grads.dX, grads.dW_router, grads.dW1, grads.dW2, routing.perm), want):
+            assert torch.equal(got, ref)
+
+
 # -------------------------------------------------------------------- AdamW
 @pytest.mark.parametrize("gdtype", [F32, BF16])
 @pytest.mark.parametrize("n", [4096 * 33 + 3, 5, 1 << 20])
