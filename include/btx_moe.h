@@ -162,8 +162,12 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
  *   W1, W3  expert e at  W + e*w13_expert_stride elements, [d,f] row-major
  *   W2      expert e at  W2 + e*w2_expert_stride elements, [f,d] row-major
  *   gates, offsets, perm, inv_pos: as written by btx_moe_route
- *   out [T,d]            dtype:  out[t] = sum_j gates[t,j] * FF_{idx[t,j]}(x[t]),
- *                        summed over j in ascending order in fp32, rounded once
+ *   residual [T,d]       dtype, may be NULL: the transformer block's input, added to the sum
+ *                        (h + FF_MoE(norm(h)) in one pass; with a capacity limit a token whose
+ *                        pairs were all dropped passes through as the residual alone).  May be x
+ *                        itself or out (elementwise in t).
+ *   out [T,d]            dtype:  out[t] = residual[t] + sum_j gates[t,j] * FF_{idx[t,j]}(x[t]),
+ *                        summed in fp32 (residual first, then j ascending), rounded once
  *   save_h1, save_h3 [R,f] dtype, grouped-row order: x W1_e and x W3_e, kept for
  *                        the backward pass.  Both NULL = forward only.
  * dtype BTX_BF16: bf16 storage, bf16 MFMA products, fp32 accumulation; the
@@ -175,7 +179,7 @@ size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int
 int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,
                        int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d, int f, int E, int k,
                        const float* gates, const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos,
-                       void* out, void* save_h1, void* save_h3,
+                       const void* residual, void* out, void* save_h1, void* save_h3,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------

@@ -34,7 +34,7 @@ _SIGNATURES = {
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),
-    "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 3 +
+    "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 4 +
                            [_vp, _sz, _vp]),
     "btx_moe_ff_backward_workspace_bytes": (_sz, [_i] * 6),
     "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u, _vp, _f] + [_vp] * 11 + [_vp] * 6 +
@@ -144,8 +144,8 @@ def _stacked(W: torch.Tensor) -> Tuple[int, int]:
 def btx_moe_ff_forward(x: torch.Tensor, W1: torch.Tensor, W3: torch.Tensor, W2: torch.Tensor, routing: Routing,
                        save: bool = True, out: Optional[torch.Tensor] = None,
                        saved: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-                       workspace: Optional[torch.Tensor] = None):
-    """Returns (out[T,d], h1, h3); h1/h3 are None when save=False."""
+                       workspace: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None):
+    """Returns (out[T,d], h1, h3); h1/h3 are None when save=False.  residual[T,d] is added to out."""
     lib = load_library()
     T, d = x.shape
     E, s13 = _stacked(W1)
@@ -162,7 +162,7 @@ def btx_moe_ff_forward(x: torch.Tensor, W1: torch.Tensor, W3: torch.Tensor, W2: 
     ws = _workspace(lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
     st = lib.btx_moe_ff_forward(_ptr(x), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f, E, k,
                                 _ptr(routing.gates), _ptr(routing.offsets), _ptr(routing.perm), _ptr(routing.inv_pos),
-                                _ptr(out), _ptr(h1), _ptr(h3), _ptr(ws), ws.numel(), _stream())
+                                _ptr(residual), _ptr(out), _ptr(h1), _ptr(h3), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_ff_forward")
     return out, h1, h3
 

@@ -149,8 +149,9 @@ size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int
 
 int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,
                        int64_t w13_expert_stride, int64_t w2_expert_stride, int T, int d, int f, int E, int k,
-                       const float* gates, const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos, void* out,
-                       void* save_h1, void* save_h3, void* workspace, size_t workspace_bytes, void* stream) {
+                       const float* gates, const int32_t* offsets, const int32_t* perm, const int32_t* inv_pos,
+                       const void* residual, void* out, void* save_h1, void* save_h3, void* workspace,
+                       size_t workspace_bytes, void* stream) {
   if (!dtype_ok(dtype) || !shapes_ok(T, d, f, E, k)) return BTX_ERR_INVALID_ARG;
   if (w13_expert_stride < (int64_t)d * f || w2_expert_stride < (int64_t)d * f) return BTX_ERR_INVALID_ARG;
   if ((save_h1 == nullptr) != (save_h3 == nullptr)) return BTX_ERR_INVALID_ARG;
@@ -169,7 +170,7 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   const RowSource xs = fused ? RowSource{x, perm, k} : RowSource{w.xs, nullptr, 1};
   BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
   BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, s));
-  BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, out, T, k, d, dtype, s));
+  BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, residual, out, T, k, d, dtype, s));
   return BTX_OK;
 }
 

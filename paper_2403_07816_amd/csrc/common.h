@@ -105,8 +105,9 @@ int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, i
 int launch_gather_rows_t(const void* src, void* dst, const int32_t* perm, const int32_t* offsets, int R, int k, int d,
                          int E, int pitch, hipStream_t s);
 // out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]   (gates NULL => unit weights; inv_pos < 0: dropped pair, skipped)
-int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d,
-                   int dtype, hipStream_t s);
+// residual (may be NULL): [T,d] added to the sum in fp32 before the one rounding
+int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, const void* residual, void* out, int T,
+                   int k, int d, int dtype, hipStream_t s);
 
 // Expert GEMM stages.  `offsets` = E+1 grouped-row offsets on the device.
 struct FfShapes { int R, d, f, E; int64_t s13, s2; };

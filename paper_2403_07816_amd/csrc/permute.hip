@@ -5,7 +5,7 @@
 //                whose contraction runs over grouped rows: dst[c][P_e + i] = src[perm[o_e + i] / k][c]
 //                for row i of expert e, with P_e = sum over e' < e of n_e' rounded up to 64 and
 //                zeros from P_e + n_e to P_(e+1).  64 rows x 128 columns are turned around in LDS.
-//   combine      out[t] = sum_j gates[t,j] * y[inv_pos[t,j]]: the gate-weighted sum of the
+//   combine      out[t] = (residual[t] +) sum_j gates[t,j] * y[inv_pos[t,j]]: the gate-weighted sum of the
 //                layer equation (Sec. 3.2), one wavefront per token row, slots summed in
 //                ascending j in fp32, one rounding.  No atomics: every output row has
 //                exactly one writer.
@@ -101,7 +101,8 @@ template <> struct Chunk<float> {
 
 template <typename ET>
 __global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restrict__ y, const float* __restrict__ gates,
-                                                           const int32_t* __restrict__ inv_pos, u32x4* __restrict__ out,
+                                                           const int32_t* __restrict__ inv_pos,
+                                                           const u32x4* __restrict__ residual, u32x4* __restrict__ out,
                                                            int T, int k, int chunks_per_row) {
   constexpr int N = Chunk<ET>::N;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
@@ -111,6 +112,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restri
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    if (residual) Chunk<ET>::unpack(residual[(size_t)t * chunks_per_row + c], acc);   // block input, added in fp32
     for (int j = 0; j < k; ++j) {
       const int r = inv_pos[(size_t)t * k + j];
       if (r < 0) continue;                  // pair dropped at its expert's capacity
@@ -145,17 +147,19 @@ int launch_gather_rows_t(const void* src, void* dst, const int32_t* perm, const 
   return BTX_OK;
 }
 
-int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, void* out, int T, int k, int d, int dtype,
-                   hipStream_t s) {
+int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, const void* residual, void* out, int T,
+                   int k, int d, int dtype, hipStream_t s) {
   const int esz = dtype == BTX_BF16 ? 2 : 4;
   const int chunks = d * esz / 16;
   dim3 grid(ceil_div(T, kThreads / kWave));
   if (dtype == BTX_BF16)
     combine_kernel<bf16_t><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
-                                                     static_cast<u32x4*>(out), T, k, chunks);
+                                                     static_cast<const u32x4*>(residual), static_cast<u32x4*>(out), T,
+                                                     k, chunks);
   else
     combine_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
-                                                    static_cast<u32x4*>(out), T, k, chunks);
+                                                    static_cast<const u32x4*>(residual), static_cast<u32x4*>(out), T,
+                                                    k, chunks);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }

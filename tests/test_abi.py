@@ -74,7 +74,7 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     null = None
 
     def fwd(T=8, d=64, f=64, E=4, k=2, s13=64 * 64, s2=64 * 64, h1=p, h3=p, ws=1 << 30, out=p):
-        return lib.btx_moe_ff_forward(p, p, p, p, 0, s13, s2, T, d, f, E, k, p, p, p, p, out, h1, h3, p, ws, null)
+        return lib.btx_moe_ff_forward(p, p, p, p, 0, s13, s2, T, d, f, E, k, p, p, p, p, null, out, h1, h3, p, ws, null)
 
     assert fwd(f=12) == 1
     assert fwd(s13=10) == 1                # expert stride smaller than one expert

@@ -82,6 +82,22 @@ def test_capacity_factor_gate_mean_statistics_fp32():
                         bias=[1.5, 0, 0, 0], cf=0.625)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_residual_is_added_in_the_combine(dtype):
+    """out = residual + FF_MoE(x) in one pass, one rounding; with a capacity limit the tokens that lost
+    all their pairs come out as the residual alone."""
+    T, d, f, E = 333, 128, 192, 4
+    L = synth.make_layer(T, d, f, E, dtype=dtype, unit_rms=True, router_bias=[2.0, 0, 0, 0])
+    G = to_dev(L)
+    res = (torch.randn(T, d, generator=torch.Generator().manual_seed(5)) * 2).to(dtype)
+    r = B.btx_moe_route(G["x"], G["W_router"], G["b_router"], None, 1, B.BTX_ROUTE_SWITCH_TOP1, capacity_factor=1.0)
+    fwd = check_route(r, L, 1, B.BTX_ROUTE_SWITCH_TOP1, 0.0, B.BTX_LB_TOKEN_FRAC, cf=1.0)
+    out, _, _ = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, save=False, residual=res.cuda())
+    assert_close(to_np(out), fwd["out"] + to_np(res), TOL[dtype], "residual + out")
+    lost = fwd["dropped"][:, 0]
+    assert lost.any() and torch.equal(out.cpu()[torch.from_numpy(lost)], res[torch.from_numpy(lost)])
+
+
 def test_expert_without_tokens_fp32():
     """A strongly negative bias starves expert 2: empty group, zero weight gradients."""
     G, r, out, g = run_layer_and_check(300, 64, 80, 4, 2, F32, bias=[0, 0, -60.0, 0])
