@@ -55,6 +55,19 @@ def test_gumbel_sample_top1_fp32(tau, lb_mode, flags):
                         bias=[0.5, 0, -0.5, 0, 0.2], tau=tau)
 
 
+def test_gumbel_at_vanishing_temperature_is_the_hard_sample():
+    """tau -> 0+: the soft sample becomes one-hot, i.e. the inference-time hard sampling (gate 1)."""
+    L = synth.make_layer(300, 64, 64, 4, dtype=F32, with_gumbel=True)
+    G = to_dev(L)
+    r = B.btx_moe_route(G["x"], G["W_router"], None, G["U"], 1, B.BTX_ROUTE_GUMBEL_TOP1, tau=1e-4)
+    noisy = O.router_logits(to_np(L["x"]), to_np(L["W_router"])) + to_np(L["U"])
+    gap = np.sort(noisy, axis=1)
+    clear = (gap[:, -1] - gap[:, -2]) > 1e-2
+    assert clear.sum() > 250
+    assert np.array_equal(r.topk_idx.cpu().numpy()[clear, 0], np.argmax(noisy, axis=1)[clear])
+    assert np.all(r.gates.cpu().numpy()[clear, 0] == 1.0)
+
+
 def test_gumbel_without_noise_at_unit_temperature_is_switch_routing():
     L = synth.make_layer(257, 64, 64, 4, dtype=F32, with_dY=True)
     G = to_dev(L)
