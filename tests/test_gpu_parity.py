@@ -179,6 +179,25 @@ def test_bf16_forward_backward(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True)
 
 
+def _random_mfma_case(i):
+    rng = np.random.default_rng(1000 + i)
+    E = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+    k = int(rng.integers(1, min(E, 4) + 1))
+    d = 32 * int(rng.integers(2, 13))
+    f = 32 * int(rng.integers(2, 20))
+    T = int(rng.integers(1, 1200))
+    return T, d, f, E, k
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_bf16_random_shapes_on_the_mfma_path(case):
+    """Seeded random shapes (d, f multiples of 32; 1-16 experts; ragged groups of every size):
+    tile edges, padded groups, the ragged strips of the tile order, BK = 32 and 64 variants."""
+    T, d, f, E, k = _random_mfma_case(case)
+    run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True, seed=synth.BASE_SEED + case,
+                        dW_dtype=F32 if case % 3 == 0 else None)
+
+
 def test_bf16_unrelated_experts_meet_the_plain_bar_on_router_gradients():
     """With experts that share nothing the gate Jacobian has no cancellation and
     dW_router / db_router must meet 2e-2 without any amplification factor."""
