@@ -45,18 +45,19 @@ struct Best { float v; int i; };
 __device__ __forceinline__ Best best_of(Best a, Best b) {
   return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
 }
-__device__ __forceinline__ Best wave_best(Best x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    Best y{__shfl_xor(x.v, o, kWave), __shfl_xor(x.i, o, kWave)};
-    x = best_of(x, y);
-  }
-  return x;
+template <int CTRL> __device__ __forceinline__ Best dpp_best(Best x) {
+  return best_of(x, Best{dpp_f32<CTRL>(x.v), dpp_i32<CTRL>(x.i)});
 }
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
+__device__ __forceinline__ Best lane_best(Best x, int lane) {
+  return Best{lane_f32(x.v, lane), __builtin_amdgcn_readlane(x.i, lane)};
+}
+// (value, index) arg-max over the wavefront; the same DPP scheme as wave_sum
+__device__ __forceinline__ Best wave_best(Best x) {
+  x = dpp_best<kDppXor1>(x);
+  x = dpp_best<kDppXor2>(x);
+  x = dpp_best<kDppRor4>(x);
+  x = dpp_best<kDppRor8>(x);
+  return best_of(best_of(lane_best(x, 0), lane_best(x, 16)), best_of(lane_best(x, 32), lane_best(x, 48)));
 }
 __device__ __forceinline__ float wave_incl_scan(float v, int lane) {
 #pragma unroll

@@ -60,9 +60,7 @@ __global__ __launch_bounds__(256) void router_ds_kernel(
     const int e = __shfl(my_e, 0, kWave);
     const float dg0 = __shfl(dg, 0, kWave);
     const float v = live ? (__logf(p) + noise[(size_t)t * E + lane]) * inv_tau : -INFINITY;
-    float vmax = v;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o, kWave));
+    const float vmax = wave_max(v);
     const float z = live ? __expf(v - vmax) : 0.f;
     const float y = z / wave_sum(z);
     const float ye = __shfl(y, e, kWave);
