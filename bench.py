@@ -39,6 +39,9 @@ VARIANTS = {
     "switch-cf1.5": dict(name="Switch top-1, router bias +2 on expert 0, capacity factor 1.5", k=1, mode=1,
                          bias=[2.0, 0.0, 0.0, 0.0], tau=1.0, cf=1.5),
     "gumbel": dict(name="Gumbel-softmax sample top-1, tau 0.5", k=1, mode=3, bias=None, tau=0.5, cf=0.0),
+    # 4 FFs split into 8 chunks each (Sec. 3.3 "Splitting Experts"): 32 experts of width 1376, top-8
+    "split8-top8": dict(name="32 split experts of width 1376, top-8", k=8, mode=0, bias=None, tau=1.0, cf=0.0, E=32,
+                        f=1376),
 }
 GEMM_STAGES = {"up_swiglu": 4, "down": 2, "bwd_act": 2, "bwd_dx": 4, "dw13": 4, "dw2": 2}   # x d*f*R flops
 
@@ -158,6 +161,7 @@ def main():
     W["T"] = args.tokens
     V = VARIANTS[args.variant]
     W["k"] = V["k"]
+    W["E"], W["f"] = V.get("E", W["E"]), V.get("f", W["f"])
     T, d, f, E, k, alpha = W["T"], W["d"], W["f"], W["E"], W["k"], W["alpha"]
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -223,7 +227,8 @@ def main():
         "value": T * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": (W["name"] if args.variant == "top2" else W["name"].replace("top-2", V["name"]))
+        "config": {"workload": (W["name"] if args.variant == "top2" else
+                                W["name"].replace("top-2", V["name"]).replace("f=11008, E=4, ", "" if "E" in V else "f=11008, E=4, "))
                    if T == WORKLOAD["T"] else f"dev run, T={T}, {V['name']}", "tokens": T, "routed_rows": R, "d_model": d,
                    "d_ff": f, "experts": E, "top_k": k},
         "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
