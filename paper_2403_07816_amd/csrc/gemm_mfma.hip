@@ -11,19 +11,21 @@
 //
 // Structure of a workgroup (WM x WN wavefronts, BM x BN x BK tile):
 //   * global -> LDS copies are direct (global_load_lds, 16 bytes per lane, no VGPR staging),
-//     NSTAGE tiles in flight, one barrier per K step;
+//     three stages of the A tile and two of the B tile; the two wavefronts of a SIMD alternate
+//     between a memory phase and a compute phase (see the main loop);
 //   * an operand whose K index is contiguous in memory is stored [row][BK] with a 16-byte
 //     chunk XOR swizzle and read with ds_read_b128; an operand whose K index is strided
-//     (weights in the forward pass, everything in the dW products) is stored as it lies in
-//     memory, [BK][cols], and read with the transposing ds_read_b64_tr_b16, so no operand is
-//     ever transposed in registers or in HBM.  The swizzles are applied by choosing which
+//     (the weights in UP and DOWN, dh1/dh3/ga in the dW products) is stored as it lies in
+//     memory, [BK][cols], and read with the transposing ds_read_b64_tr_b16; x and dY reach the
+//     dW products already transposed and zero-padded per expert.  The swizzles are applied by choosing which
 //     global chunk each lane fetches, since a direct copy fixes the LDS position per lane;
 //   * v_mfma_f32_32x32x16_bf16 with the roles of the operands swapped (the N-side fragment is
 //     passed first), so that each lane ends up with 4 consecutive output columns of one row
 //     and stores 8 bytes at a time;
 //   * grouped rows: tiles are enumerated per expert on the device (no host sync); a tile past
 //     the last one exits.  Rows beyond a group's end are loaded from a clamped address and
-//     never stored.  In the dW products the K tail is zeroed in registers.
+//     never stored.  A last k tile that is half empty (K = 32 mod 64) has its copies re-pointed
+//     at valid data and the A fragments of its empty half zeroed in registers.
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
 
@@ -98,7 +100,7 @@ __device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
   return (uint32_t)(r * ROWB + ((chunk ^ (((r / RP) * STEP) & (CPR - 1))) << 4));
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 struct Gemm {
   // K index contiguous in memory?  In the dW products K is the grouped-row index: the operand
   // with d columns (x for dW1/dW3, dY for dW2) arrives transposed, [d][padded rows], every
@@ -113,24 +115,19 @@ struct Gemm {
   static constexpr int TNH = DUAL ? TN / 2 : TN;
   static constexpr int BNH = DUAL ? BN / 2 : BN;               // output columns per B panel
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  // LDS: NSA stages of the A tile, then NSB stages of the B tile.  NSA == NSB: plain
-  // multi-stage pipeline.  NSA == 3, NSB == 2 (8 wavefronts, BK == 64): ping-pong schedule.
+  // LDS: NSA = 3 stages of the A tile, then NSB = 2 stages of the B tile (the ping-pong schedule)
   static constexpr int B_BASE = NSA * A_BYTES;
   static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
-  static constexpr bool PINGPONG = (NSA == 3 && NSB == 2);
-  static constexpr int NSTAGE = NSB;
-  static_assert(PINGPONG || NSA == NSB, "stage counts");
-  static_assert(!PINGPONG || (WM * WN == 8 && BK == 64), "ping-pong needs 8 wavefronts and 4 k steps");
+  static_assert(NSA == 3 && NSB == 2 && WM * WN == 8 && BK == 64, "the schedule is written for 8 wavefronts, 4 k steps");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   static constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // per wavefront per tile
   static constexpr int KSTEPS = BK / 16;
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split into 1 KB wave copies");
   static_assert(TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "bad wave tiling");
-  static_assert(BK == 32 || BK == 64, "BK");
 
   // ---- LDS addressing ----------------------------------------------------
   // K-contiguous tile: [rows][BK], 16-byte chunks XOR-swizzled by row
-  static __device__ __forceinline__ int kc_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  static __device__ __forceinline__ int kc_swz(int row) { return (row >> 1) & 7; }
   // strided-K tile: [BK][COLS], 16-byte chunk index XORed with (k & 3) << 2
 
   // byte offset inside a wave's copy `seg` (1 KB each) -> global element offset, for both layouts
@@ -244,6 +241,7 @@ struct Gemm {
     uint32_t a_off[A_LOADS], b_off[B_LOADS];
     int a_k[A_LOADS], b_k[B_LOADS], a_c[A_LOADS], b_c[B_LOADS];   // strided layouts: k row / column
     bool b_second[B_LOADS];
+    bool a_hi[A_LOADS], b_hi[B_LOADS];                            // KC layouts: chunk lies in the upper 32 k of the tile
 #pragma unroll
     for (int q = 0; q < A_LOADS; ++q) {
       int major, minor;
@@ -254,7 +252,9 @@ struct Gemm {
         a_off[q] = g.a_perm ? (uint32_t)(g.a_perm[gr] / g.a_k) * (uint32_t)(g.lda * 2) + (uint32_t)(minor * 2)
                             : (uint32_t)((gr - row0) * g.lda + minor) * 2u;
         a_k[q] = a_c[q] = 0;
+        a_hi[q] = minor >= 32;
       } else {
+        a_hi[q] = false;
         a_k[q] = major;
         a_c[q] = min(row0 + minor, row_end - 8);
         a_off[q] = (uint32_t)(major * g.lda + a_c[q]) * 2u;
@@ -273,7 +273,9 @@ struct Gemm {
         b_off[q] = (uint32_t)((min(col0 + major, g.N - 1) - col0) * g.ldb + minor) * 2u;
         b_k[q] = b_c[q] = 0;
         b_second[q] = false;
+        b_hi[q] = minor >= 32;
       } else {
+        b_hi[q] = false;
         b_k[q] = major;
         b_c[q] = min(col0 + minor, g.N - 8);
         b_off[q] = (uint32_t)(major * g.ldb + b_c[q]) * 2u;
@@ -284,6 +286,13 @@ struct Gemm {
     const int k_len = k_end - k_begin;
     const int nk1 = (k_len + BK - 1) / BK;
     const int nk = MODE == BWD_DX ? 2 * nk1 : nk1;
+    // K is a multiple of 32 (of 64 in the dW products, whose rows are padded): when it is not
+    // a multiple of 64 the last k tile of a pass is half empty.  Its copies are re-pointed at
+    // the valid half (any finite data will do) and the A fragments of its second half are
+    // zeroed in registers, so those k steps add nothing.
+    // TAIL is a template parameter: the common shapes pay nothing for it.
+    static_assert(!(TAIL && GROUP_K), "the dW products have no K tail");
+    auto is_tail = [&](int kt) { return TAIL && (kt == nk1 - 1 || kt == nk - 1); };
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
 
     // Copies of the A / B part of tile kt into LDS stage kt % NSA / kt % NSB.
@@ -300,8 +309,9 @@ struct Gemm {
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
         uint32_t off = a_off[q];
-        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it is zeroed later)
+        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it meets zeros)
         if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
+        if (A_KC && a_hi[q] && is_tail(kt)) off -= 64u;
         copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
       }
     };
@@ -315,6 +325,10 @@ struct Gemm {
       for (int q = 0; q < B_LOADS; ++q) {
         uint32_t off = b_off[q];
         if (GROUP_K && !B_KC) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
+        if (is_tail(kt)) {
+          if (B_KC) { if (b_hi[q]) off -= 64u; }
+          else off = (uint32_t)(min(b_k[q], 31) * g.ldb + b_c[q]) * 2u;
+        }
         const bool second = MODE == BWD_DX ? pass2 : (DUAL && b_second[q]);
         copy16_to_lds(second ? B1b : B0b, off, stage + (wave * B_LOADS + q) * 1024);
       }
@@ -351,7 +365,7 @@ struct Gemm {
     };
     // grouped-K: the k rows past an expert's last one meet the zero fill of the transposed operand
 
-    if constexpr (PINGPONG) {
+    {
       // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) alternate
       // between a memory phase (LDS fragment reads of half a tile + a quarter of the copies
       // of a later tile) and a compute phase (an uninterrupted run of 16 MFMAs), half a period
@@ -387,6 +401,14 @@ struct Gemm {
           if (h == 0 && kt + 1 < nk) issueB(kt + 1);
           if (h == 1 && kt + 2 < nk) issueA(kt + 2);
           __builtin_amdgcn_s_waitcnt(0xC07F);        // lgkmcnt(0): fragments are in registers
+          if (h == 1 && is_tail(kt)) {               // the half of the last k tile that lies past K
+#pragma unroll
+            for (int x = 0; x < HS; ++x)
+#pragma unroll
+              for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 8; ++v) fa[x][i][v] = (__bf16)0.0f;
+          }
           if (h == 1 && grp == 1) { if (kt + 2 < nk) wait_vmcnt(A_LOADS); else wait_vmcnt(0); }
           __builtin_amdgcn_sched_barrier(0);
           __builtin_amdgcn_s_barrier();
@@ -400,43 +422,6 @@ struct Gemm {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-    } else {
-      // Plain NSTAGE-deep pipeline, one barrier per tile.  The loop is rotated by one k step:
-      // the MFMAs of a tile's last k step run after the barrier that publishes the next tile,
-      // right behind the LDS reads of that tile's first fragments.
-      static_assert(KSTEPS % 2 == 0, "fragment double buffer assumes an even number of k steps");
-      constexpr int PER_TILE = A_LOADS + B_LOADS;
-      // wait until tile kt has landed (up to NSTAGE-2 younger tiles may stay in flight) and
-      // publish it; passing the barrier also means every wavefront is done reading tile kt-1
-      auto publish = [&](int kt) {
-        if (kt + NSTAGE - 2 < nk) wait_vmcnt((NSTAGE - 2) * PER_TILE);
-        else wait_vmcnt(0);
-        __syncthreads();
-      };
-#pragma unroll
-      for (int s = 0; s < NSTAGE - 1; ++s)
-        if (s < nk) { issueA(s); issueB(s); }
-      bf16x8 af[2][TM], bfr[2][TN];
-      if (nk > 0) {
-        publish(0);
-        load_frags(0, 0, af[0], bfr[0]);
-      }
-      for (int kt = 0; kt < nk; ++kt) {
-        // the stage of tile kt+NSTAGE-1 was last read for tile kt-1: free since the last barrier
-        if (kt + NSTAGE - 1 < nk) { issueA(kt + NSTAGE - 1); issueB(kt + NSTAGE - 1); }
-#pragma unroll
-        for (int ks = 0; ks + 1 < KSTEPS; ++ks) {
-          const int cur = ks & 1;
-          load_frags(kt, ks + 1, af[cur ^ 1], bfr[cur ^ 1]);
-          mfma_step(af[cur], bfr[cur]);
-        }
-        constexpr int last = (KSTEPS - 1) & 1;       // fragments of the last k step, still to multiply
-        if (kt + 1 < nk) {
-          publish(kt + 1);
-          load_frags(kt + 1, 0, af[last ^ 1], bfr[last ^ 1]);
-        }
-        mfma_step(af[last], bfr[last]);
-      }
     }
 
     // ---- epilogue ----------------------------------------------------------
@@ -449,7 +434,6 @@ struct Gemm {
     // bytes per row).  BWD_ACT fetches the saved h1/h3 band the same way round.  The operand
     // stages are dead by now: in the ping-pong schedule the barrier that ends group 0's last
     // compute phase comes after group 1's last fragment read and after every copy has landed.
-    if (!PINGPONG) __syncthreads();
     const int lane_m = lane & 31, lane_h = lane >> 5;
     const int wcol0 = col0 + wn * (TNH * 32);         // first output column of this wavefront (per panel)
     float dg_acc[TM];
@@ -619,15 +603,15 @@ struct Gemm {
   }
 };
 
-template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 __global__ __launch_bounds__(WM* WN* kWave) void mfma_gemm_kernel(MArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE>::run(g, smem);
+  Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>::run(g, smem);
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE>
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 int launch(MArgs g, hipStream_t s) {
-  using G = Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
+  using G = Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
   constexpr int BNH = G::DUAL ? BN / 2 : BN;
   g.tiles_n = ceil_div(g.N, BNH);
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
@@ -636,7 +620,7 @@ int launch(MArgs g, hipStream_t s) {
   // every tile has exactly one block id below (number of tiles) + 8; see the tile mapping
   g.blocks_per_e = (int)align_up((size_t)g.tiles_m * g.tiles_n, 8) + 8;
   const int total = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
-  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE>;
+  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
   static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -649,8 +633,8 @@ int launch(MArgs g, hipStream_t s) {
   return BTX_OK;
 }
 
-// The direct-copy loaders need whole 16-byte chunks inside every row and K multiples of BK
-// where K is a matrix dimension.
+// The direct-copy loaders need whole 16-byte chunks inside every row and K multiples of 32
+// where K is a matrix dimension (half a k tile).
 bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh.d >= 64 && sh.f >= 64; }
 
 }  // namespace
@@ -667,7 +651,7 @@ int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const in
   g.A0 = (const bf16_t*)xs.base; g.a_perm = xs.perm; g.a_k = xs.k; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
-  return sh.d % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, UP>(g, s);
+  return sh.d % 64 ? launch<256, 256, 64, 2, 4, 3, 2, UP, true>(g, s) : launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s);
 }
 
 int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s) {
@@ -676,7 +660,7 @@ int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShape
   g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.d; g.ldc = sh.d;
   g.strideB_e = sh.s2; g.R = sh.R;
-  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, DOWN>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, DOWN>(g, s);
+  return sh.f % 64 ? launch<256, 256, 64, 2, 4, 3, 2, DOWN, true>(g, s) : launch<256, 256, 64, 2, 4, 3, 2, DOWN>(g, s);
 }
 
 int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
@@ -690,8 +674,8 @@ int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const voi
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
   g.strideB_e = sh.s2; g.R = sh.R;
-  return sh.d % 64 == 0 ? launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT>(g, s)
-                        : launch<256, kActBN, 32, 2, 4, 4, 4, BWD_ACT>(g, s);
+  return sh.d % 64 ? launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT, true>(g, s)
+                   : launch<256, kActBN, 64, 2, 4, 3, 2, BWD_ACT>(g, s);
 }
 
 int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
@@ -701,7 +685,8 @@ int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3
   g.A0 = (const bf16_t*)dh1; g.A1 = (const bf16_t*)dh3; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = dxs;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.f; g.ldc = sh.d;
   g.strideB_e = sh.s13; g.R = sh.R;
-  return sh.f % 64 == 0 ? launch<256, 256, 64, 2, 4, 3, 2, BWD_DX>(g, s) : launch<256, 256, 32, 2, 4, 4, 4, BWD_DX>(g, s);
+  return sh.f % 64 ? launch<256, 256, 64, 2, 4, 3, 2, BWD_DX, true>(g, s)
+                   : launch<256, 256, 64, 2, 4, 3, 2, BWD_DX>(g, s);
 }
 
 int mfma_dw_pitch(int R, int E) { return (int)align_up((size_t)R, 64) + 64 * E; }

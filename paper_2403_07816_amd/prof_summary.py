@@ -16,8 +16,8 @@ MODES = {0: "up_swiglu", 1: "down", 2: "bwd_act", 3: "bwd_dx", 4: "dw13", 5: "dw
 def short(name: str) -> str:
     name = name.replace("btx::(anonymous namespace)::", "").replace("void ", "").split("(")[0]
     if name.startswith("mfma_gemm_kernel<"):
-        args = name[len("mfma_gemm_kernel<"):-1].split(",")
-        name += " " + MODES.get(int(args[-1]), "?")
+        args = name[len("mfma_gemm_kernel<"):-1].split(",")   # BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL
+        name += " " + MODES.get(int(args[7]), "?")
     return name
 
 
