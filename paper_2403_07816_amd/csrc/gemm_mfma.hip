@@ -621,12 +621,16 @@ int launch(MArgs g, hipStream_t s) {
   g.blocks_per_e = (int)align_up((size_t)g.tiles_m * g.tiles_n, 8) + 8;
   const int total = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
   auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
-  static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-  if (!attr_set) {
+  // The dynamic LDS limit is raised once per device (idempotent, so a race between threads is
+  // harmless); it must not be set inside a stream capture, so the first call comes before one.
+  static bool attr_set[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BTX_ERR_HIP;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             G::LDS_BYTES) != hipSuccess)
       return BTX_ERR_HIP;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   kern<<<total, G::NT, G::LDS_BYTES, s>>>(g);
   BTX_LAUNCH_CHECK();
