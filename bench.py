@@ -143,6 +143,42 @@ def cpu_baseline(L, W, sample_tokens):
             "sample": f"first {sample_tokens} tokens of the same batch, fwd+bwd in fp64 numpy, {dt:.1f} s"}
 
 
+def library_gemm_context(L, R, d, f, reps=10):
+    """Context only: the vendor library's plain GEMMs (torch.matmul) on the shapes of the six expert
+    products, all R rows against one expert's weights, no grouping and no fused epilogue.  Not part
+    of the measured path and never compared as a target: it shows what a tuned dense GEMM reaches on
+    the same box, data and clock."""
+    dev = L["x"].device
+    xs = L["x"].repeat((R + L["x"].shape[0] - 1) // L["x"].shape[0], 1)[:R].contiguous()
+    dys = L["dY"].repeat((R + L["dY"].shape[0] - 1) // L["dY"].shape[0], 1)[:R].contiguous()
+    W1, W3, W2 = L["W1"][0], L["W3"][0], L["W2"][0]
+    a = torch.randn((R, f), device=dev, dtype=torch.float32).bfloat16()
+    cases = {
+        "up_swiglu": (4, lambda: (xs @ W1, xs @ W3)),
+        "down": (2, lambda: a @ W2),
+        "bwd_act": (2, lambda: dys @ W2.t()),
+        "bwd_dx": (4, lambda: (a @ W1.t(), a @ W3.t())),
+        "dw13": (4, lambda: (xs.t() @ a, xs.t() @ a)),
+        "dw2": (2, lambda: a.t() @ dys),
+    }
+    out = {}
+    for name, (c, fn) in cases.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = {"ms": ms, "tflops": c * d * f * R / (ms * 1e-3) / 1e12}
+    total = sum(v["ms"] for v in out.values())
+    return {"kind": "torch.matmul, dense, one expert's weights, no fused epilogue (context, not a target)",
+            "ms": total, "tflops": 18.0 * d * f * R / (total * 1e-3) / 1e12, "per_kernel": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,6 +188,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--variant", default="top2", choices=sorted(VARIANTS),
                     help="routing variant; only top2 is the benchmark of record, the others are extra measurements")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library's plain GEMMs on the same shapes (context only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -247,6 +285,8 @@ def main():
     }
     if args.cpu_sample > 0 and args.variant == "top2":   # the oracle is timed on the benchmark configuration only
         result["cpu_baseline"] = cpu_baseline(L, W, min(args.cpu_sample, T))
+    if args.library_gemm:
+        result["library_gemm"] = library_gemm_context(L, R, d, f)
     print(json.dumps(result))
 
 
