@@ -23,6 +23,7 @@ What each function follows:
                    layer by gradient descent)
   split_experts    Sec. 3.3 "Splitting Experts"
   merge_average    Sec. 3.2: non-FF parameters are averaged elementwise
+  merge_weighted   the same merge with caller-chosen coefficients
   grouping         the token->expert grouping implied by skipping zero gates
 
 Readings where the paper is silent (also listed in the design notes):
@@ -430,6 +431,18 @@ def merge_average(tensors: Sequence[np.ndarray]) -> np.ndarray:
     for t in tensors:
         acc = acc + np.asarray(t, F64)
     return acc / len(tensors)
+
+
+def merge_weighted(tensors: Sequence[np.ndarray], weights: Sequence[float]) -> np.ndarray:
+    """Elementwise weighted sum  sum_n w_n * tensors[n]  in float64, terms added in input
+    order.  Generalises the uniform mean of Sec. 3.2 (w_n = 1/N) to caller-chosen
+    coefficients; the paper itself only averages, so whether the authors ever weighted a
+    merge is parity unpinned.  The weights are taken as given (not normalised)."""
+    assert len(tensors) == len(weights) and len(tensors) >= 1
+    acc = np.zeros_like(np.asarray(tensors[0], F64))
+    for t, w in zip(tensors, weights):
+        acc = acc + np.float64(w) * np.asarray(t, F64)
+    return acc
 
 
 def adamw_step(p, g, m, v, step: int, lr: float, beta1: float, beta2: float, eps: float, weight_decay: float):

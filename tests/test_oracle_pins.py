@@ -508,6 +508,22 @@ def test_merge_average():
     assert np.array_equal(O.merge_average(ints), np.array([3.0, 2.0, -1.0]))
 
 
+def test_merge_weighted():
+    """Pins: a one-hot weight selects that model; uniform weights 1/N (exact in binary) give the
+    mean; small integers come out exactly; np.average (a library routine) agrees when the
+    weights sum to one; the result is linear in the weights."""
+    ts = [RNG.normal(size=(6, 5)) for _ in range(4)]
+    assert np.array_equal(O.merge_weighted(ts, [0, 0, 1, 0]), ts[2])
+    assert np.array_equal(O.merge_weighted(ts, [0.25] * 4), O.merge_average(ts))
+    ints = [np.array([1.0, 2.0, -8.0]), np.array([3.0, 2.0, 4.0])]
+    assert np.array_equal(O.merge_weighted(ints, [2.0, -1.0]), np.array([-1.0, 2.0, -20.0]))
+    w = [0.5, 0.25, 0.125, 0.125]
+    np.testing.assert_allclose(O.merge_weighted(ts, w), np.average(np.stack(ts), axis=0, weights=w), rtol=1e-14)
+    w2 = [0.1, -0.3, 0.7, 0.2]
+    np.testing.assert_allclose(O.merge_weighted(ts, [a + 2 * b for a, b in zip(w, w2)]),
+                               O.merge_weighted(ts, w) + 2 * O.merge_weighted(ts, w2), rtol=1e-13, atol=1e-15)
+
+
 def test_round_to_bf16_matches_torch_and_rounds_once():
     import torch
     v = RNG.normal(size=10000) * np.exp(RNG.normal(size=10000) * 5)
