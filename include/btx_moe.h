@@ -231,6 +231,23 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
 int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * btx_merge_weighted - the merge of Sec. 3.2 with caller-chosen coefficients:
+ * out = sum_n weights[n] * inputs[n], elementwise.  (The paper only averages;
+ * this is the same pass with the 1/N replaced by a weight per model, e.g. to
+ * favour the seed model or a domain.  The weights are used as given, they are
+ * not normalised.)
+ *
+ *   inputs   HOST array of N device pointers, each [numel] of dtype
+ *   weights  HOST array of N finite floats
+ *   out      [numel] dtype; may alias any inputs[i]
+ * The sum is accumulated in fp64 in input order (every product is exact there)
+ * and rounded once to the storage type, for bf16 without a detour through fp32.
+ * Requirements: 1 <= N <= 16, numel >= 0, pointers aligned to 16 bytes.
+ */
+int btx_merge_weighted(const void* const* inputs, const float* weights, int N, void* out, int64_t numel, int dtype,
+                       void* stream);
+
+/* ---------------------------------------------------------------------------
  * btx_mix_experts - MiX construction utilities of Sec. 3.3: "Splitting Experts"
  * (each of the N FFs is cut along d_ff into C chunks, giving N*C experts of width
  * f/C: expert i*C+c owns columns [c*f/C, (c+1)*f/C) of W1_i and W3_i and the same

@@ -40,6 +40,7 @@ _SIGNATURES = {
     "btx_moe_ff_backward": (_i, [_vp] * 6 + [_i, _i64, _i64] + [_i] * 7 + [_f, _f, _u, _vp, _f] + [_vp] * 11 + [_vp] * 6 +
                             [_i, _vp, _sz, _vp]),
     "btx_merge_average": (_i, [ctypes.POINTER(_vp), _i, _vp, _i64, _i, _vp]),
+    "btx_merge_weighted": (_i, [ctypes.POINTER(_vp), ctypes.POINTER(ctypes.c_float), _i, _vp, _i64, _i, _vp]),
     "btx_adamw_step": (_i, [_vp, _vp, _vp, _vp, _i, _vp, _i64, _i, _f, _f, _f, _f, _f, _vp]),
     "btx_mix_experts": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]),
 }
@@ -219,6 +220,21 @@ def btx_merge_average(tensors: Sequence[torch.Tensor], out: Optional[torch.Tenso
     arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
     st = lib.btx_merge_average(arr, len(tensors), _ptr(out), t0.numel(), _dtype_code(t0), _stream())
     _check(st, "btx_merge_average")
+    return out
+
+
+def btx_merge_weighted(tensors: Sequence[torch.Tensor], weights: Sequence[float],
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    lib = load_library()
+    t0 = tensors[0]
+    assert len(weights) == len(tensors)
+    for t in tensors:
+        assert t.shape == t0.shape and t.dtype == t0.dtype and t.is_cuda and t.is_contiguous()
+    out = out if out is not None else torch.empty_like(t0)
+    arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+    wts = (ctypes.c_float * len(tensors))(*[float(w) for w in weights])
+    st = lib.btx_merge_weighted(arr, wts, len(tensors), _ptr(out), t0.numel(), _dtype_code(t0), _stream())
+    _check(st, "btx_merge_weighted")
     return out
 
 

@@ -243,6 +243,18 @@ int btx_merge_average(const void* const* inputs, int N, void* out, int64_t numel
   return launch_merge_average(inputs, N, out, numel, dtype, static_cast<hipStream_t>(stream));
 }
 
+int btx_merge_weighted(const void* const* inputs, const float* weights, int N, void* out, int64_t numel, int dtype,
+                       void* stream) {
+  if (!dtype_ok(dtype) || N < 1 || N > 16 || numel < 0 || !inputs || !weights) return BTX_ERR_INVALID_ARG;
+  for (int n = 0; n < N; ++n)
+    if (!(weights[n] == weights[n]) || weights[n] > 3.0e38f || weights[n] < -3.0e38f) return BTX_ERR_INVALID_ARG;
+  if (numel == 0) return BTX_OK;
+  if (!out || ((uintptr_t)out & 15)) return BTX_ERR_INVALID_ARG;
+  for (int n = 0; n < N; ++n)
+    if (!inputs[n] || ((uintptr_t)inputs[n] & 15)) return BTX_ERR_INVALID_ARG;
+  return launch_merge_weighted(inputs, weights, N, out, numel, dtype, static_cast<hipStream_t>(stream));
+}
+
 int btx_adamw_step(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, int64_t numel,
                    int step, float lr, float beta1, float beta2, float eps, float weight_decay, void* stream) {
   if (!dtype_ok(grad_dtype) || numel < 0 || step < 1) return BTX_ERR_INVALID_ARG;

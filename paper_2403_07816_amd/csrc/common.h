@@ -182,5 +182,7 @@ int launch_mix_experts(const void* W1, const void* W3, const void* W2, int dtype
 int launch_adamw(float* P, float* M, float* V, const void* G, int grad_dtype, void* lowp, int64_t n, int step, float lr,
                  float beta1, float beta2, float eps, float wd, hipStream_t s);
 int launch_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, hipStream_t s);
+int launch_merge_weighted(const void* const* inputs, const float* weights, int N, void* out, int64_t numel, int dtype,
+                          hipStream_t s);
 
 }  // namespace btx

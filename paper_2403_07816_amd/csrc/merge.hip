@@ -78,7 +78,93 @@ __global__ __launch_bounds__(256) void merge_f32_kernel(Ptrs in, int N, float* _
   }
 }
 
+// Weighted merge: sum_n w_n * in_n, accumulated in fp64 in input order (every product of a
+// float weight and a bf16 / fp32 value is exact in fp64, so the sum is the same fp64 number a
+// host computes in that order) and rounded once to the storage type.
+struct Weights { float w[kMaxInputs]; };
+
+// fp64 -> bf16, one rounding: through fp32 first would round twice, which only matters when the
+// fp32 value is an exact bf16 tie; the sign of what the first rounding dropped settles that case.
+__device__ __forceinline__ bf16_t f64_to_bf16(double v) {
+  const float q = (float)v;
+  uint32_t u = __float_as_uint(q);
+  if ((u & 0xffffu) == 0x8000u) {
+    const double r = v - (double)q;
+    if (r != 0.0) {
+      const bool up = (r > 0.0) == (q > 0.f);
+      return (bf16_t)((u >> 16) + (up ? 1u : 0u));
+    }
+  }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__global__ __launch_bounds__(256) void merge_weighted_bf16_kernel(Ptrs in, Weights wt, int N, bf16_t* __restrict__ out,
+                                                                   int64_t numel) {
+  const int64_t nchunk = numel / 8;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunk; c += (int64_t)gridDim.x * blockDim.x) {
+    double acc[8] = {};
+    for (int n = 0; n < N; ++n) {
+      const u32x4 w = static_cast<const u32x4*>(in.p[n])[c];
+      const double wn = (double)wt.w[n];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += wn * (double)bf16lo(w[i]);
+        acc[2 * i + 1] += wn * (double)bf16hi(w[i]);
+      }
+    }
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (uint32_t)f64_to_bf16(acc[2 * i]) | ((uint32_t)f64_to_bf16(acc[2 * i + 1]) << 16);
+    reinterpret_cast<u32x4*>(out)[c] = o;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (int)(numel - nchunk * 8)) {  // ragged tail
+    const int64_t i = nchunk * 8 + threadIdx.x;
+    double a = 0.0;
+    for (int n = 0; n < N; ++n) a += (double)wt.w[n] * (double)bf16_to_f32(static_cast<const bf16_t*>(in.p[n])[i]);
+    out[i] = f64_to_bf16(a);
+  }
+}
+
+__global__ __launch_bounds__(256) void merge_weighted_f32_kernel(Ptrs in, Weights wt, int N, float* __restrict__ out,
+                                                                  int64_t numel) {
+  const int64_t nchunk = numel / 4;
+  for (int64_t c = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; c < nchunk; c += (int64_t)gridDim.x * blockDim.x) {
+    double acc[4] = {};
+    for (int n = 0; n < N; ++n) {
+      const f32x4 v = static_cast<const f32x4*>(in.p[n])[c];
+      const double wn = (double)wt.w[n];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] += wn * (double)v[i];
+    }
+    f32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (float)acc[i];
+    reinterpret_cast<f32x4*>(out)[c] = o;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (int)(numel - nchunk * 4)) {
+    const int64_t i = nchunk * 4 + threadIdx.x;
+    double a = 0.0;
+    for (int n = 0; n < N; ++n) a += (double)wt.w[n] * (double)static_cast<const float*>(in.p[n])[i];
+    out[i] = (float)a;
+  }
+}
+
 }  // namespace
+
+int launch_merge_weighted(const void* const* inputs, const float* weights, int N, void* out, int64_t numel, int dtype,
+                          hipStream_t s) {
+  Ptrs p{};
+  Weights w{};
+  for (int n = 0; n < N; ++n) { p.p[n] = inputs[n]; w.w[n] = weights[n]; }
+  const int per = dtype == BTX_BF16 ? 8 : 4;
+  const int64_t chunks = numel / per;
+  const int grid = (int)std::min<int64_t>(std::max<int64_t>((chunks + 255) / 256, 1), 256 * 32);
+  if (dtype == BTX_BF16) merge_weighted_bf16_kernel<<<grid, 256, 0, s>>>(p, w, N, static_cast<bf16_t*>(out), numel);
+  else merge_weighted_f32_kernel<<<grid, 256, 0, s>>>(p, w, N, static_cast<float*>(out), numel);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
 
 int launch_merge_average(const void* const* inputs, int N, void* out, int64_t numel, int dtype, hipStream_t s) {
   Ptrs p{};

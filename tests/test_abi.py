@@ -107,6 +107,16 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert lib.btx_merge_average(arr, 2, p, 0, 0, null) == 0
     assert lib.btx_merge_average(arr, 2, p, -1, 0, null) == 1
 
+    wts = (ctypes.c_float * 2)(0.5, 0.5)
+    assert lib.btx_merge_weighted(arr, wts, 0, p, 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, wts, 17, p, 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, None, 2, p, 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, (ctypes.c_float * 2)(0.5, float("nan")), 2, p, 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, (ctypes.c_float * 2)(0.5, float("inf")), 2, p, 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, wts, 2, ctypes.c_void_p(257), 16, 0, null) == 1
+    assert lib.btx_merge_weighted(arr, wts, 2, p, 0, 0, null) == 0
+    assert lib.btx_merge_weighted(arr, wts, 2, p, -1, 0, null) == 1
+
 
 def test_mix_experts_rejects_bad_arguments(lib):
     bad = 1

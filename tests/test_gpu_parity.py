@@ -267,6 +267,31 @@ def test_merge_in_place():
     assert torch.equal(sets[0], want)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("weights", [[0.5, 0.25, 0.25], [0.7, 0.1, 0.15, 0.05], [1.0], [2.0, -1.0], [0.3, 0.3, 0.3, 0.3, 0.3]])
+def test_weighted_merge_matches_the_oracle_bit_for_bit(dtype, weights):
+    """fp64 accumulation in input order on both sides (every product is exact in fp64) and one
+    rounding to the storage type: the results must be identical, ragged tail included."""
+    sets = synth.make_merge_set([(257, 131)], len(weights), dtype=dtype)[0]
+    w32 = [float(np.float32(w)) for w in weights]            # the ABI takes float weights
+    acc = O.merge_weighted([to_np(t) for t in sets], w32)
+    want = O.round_to_bf16(acc) if dtype == BF16 else acc.astype(np.float32)
+    got = B.btx_merge_weighted([t.cuda() for t in sets], weights)
+    assert np.array_equal(got.float().cpu().numpy(), want)
+
+
+def test_weighted_merge_special_cases():
+    sets = [t.cuda() for t in synth.make_merge_set([(300, 77)], 4, dtype=BF16)[0]]
+    # a one-hot weight vector selects that model, bit for bit
+    assert torch.equal(B.btx_merge_weighted(sets, [0.0, 0.0, 1.0, 0.0]), sets[2])
+    # weights 1/4 are exact in binary: the weighted merge then is the plain average
+    assert torch.equal(B.btx_merge_weighted(sets, [0.25] * 4), B.btx_merge_average(sets))
+    # in place
+    want = B.btx_merge_weighted(sets, [0.4, 0.3, 0.2, 0.1])
+    B.btx_merge_weighted(sets, [0.4, 0.3, 0.2, 0.1], out=sets[0])
+    assert torch.equal(sets[0], want)
+
+
 # ------------------------------------------------------------- split / blend
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("N,d,f,C", [(4, 64, 96, 3), (2, 40, 36, 2), (3, 24, 30, 5), (1, 16, 64, 8)])
