@@ -22,6 +22,7 @@ What each function follows:
                    fixed (the paper writes no backward; it only finetunes the
                    layer by gradient descent)
   split_experts    Sec. 3.3 "Splitting Experts"
+  rmsnorm          the pre-normalisation in front of the sublayer (seed model, Sec. 4.1)
   merge_average    Sec. 3.2: non-FF parameters are averaged elementwise
   merge_weighted   the same merge with caller-chosen coefficients
   grouping         the token->expert grouping implied by skipping zero gates
@@ -431,6 +432,31 @@ def merge_average(tensors: Sequence[np.ndarray]) -> np.ndarray:
     for t in tensors:
         acc = acc + np.asarray(t, F64)
     return acc / len(tensors)
+
+
+def rmsnorm(h: np.ndarray, gain: np.ndarray, eps: float):
+    """Root-mean-square normalisation of every token row, the pre-normalisation in front of
+    the feed-forward sublayer of the seed model's blocks (Sec. 4.1: Llama-2 7B):
+        xn[t,c] = h[t,c] * rstd[t] * gain[c],   rstd[t] = 1 / sqrt(mean_c h[t,c]^2 + eps).
+    Returns (xn [T,d], rstd [T]) in float64.  The block then computes
+    out = h + FF_MoE(xn): the layer of Sec. 3.2 takes xn where that section writes x."""
+    h = np.asarray(h, F64)
+    gain = np.asarray(gain, F64)
+    rstd = 1.0 / np.sqrt(np.mean(h * h, axis=1) + eps)
+    return h * rstd[:, None] * gain[None, :], rstd
+
+
+def rmsnorm_backward(dxn: np.ndarray, h: np.ndarray, gain: np.ndarray, eps: float):
+    """Chain rule through rmsnorm: with xhat = h * rstd and q = gain * dxn,
+        dh[t]    = rstd[t] * (q[t] - xhat[t] * mean_c(q[t,c] * xhat[t,c])),
+        dgain[c] = sum_t dxn[t,c] * xhat[t,c].
+    Returns (dh [T,d], dgain [d]) in float64."""
+    dxn, h, gain = np.asarray(dxn, F64), np.asarray(h, F64), np.asarray(gain, F64)
+    rstd = 1.0 / np.sqrt(np.mean(h * h, axis=1) + eps)
+    xhat = h * rstd[:, None]
+    q = dxn * gain[None, :]
+    dh = rstd[:, None] * (q - xhat * np.mean(q * xhat, axis=1, keepdims=True))
+    return dh, np.sum(dxn * xhat, axis=0)
 
 
 def merge_weighted(tensors: Sequence[np.ndarray], weights: Sequence[float]) -> np.ndarray:

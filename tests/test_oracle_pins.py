@@ -508,6 +508,52 @@ def test_merge_average():
     assert np.array_equal(O.merge_average(ints), np.array([3.0, 2.0, -1.0]))
 
 
+# ------------------------------------------------------------------ rmsnorm --
+def test_rmsnorm_against_the_library_routine_and_its_invariants():
+    import torch
+    h = RNG.normal(size=(7, 24)) * np.exp(RNG.normal(size=(7, 1)))
+    gain = 1.0 + 0.1 * RNG.normal(size=24)
+    xn, rstd = O.rmsnorm(h, gain, 1e-5)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(h), (24,), torch.from_numpy(gain), 1e-5).numpy()
+    np.testing.assert_allclose(xn, ref, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(rstd, 1.0 / np.sqrt((h * h).mean(axis=1) + 1e-5), rtol=1e-14)
+    # unit gain, no eps: every row has mean square 1, and scaling a row changes nothing
+    x1, _ = O.rmsnorm(h, np.ones(24), 0.0)
+    np.testing.assert_allclose((x1 * x1).mean(axis=1), 1.0, rtol=1e-13)
+    x2, _ = O.rmsnorm(h * np.array([[3.0], [0.5], [7.0], [1.0], [2.0], [11.0], [0.25]]), np.ones(24), 0.0)
+    np.testing.assert_allclose(x2, x1, rtol=1e-13, atol=1e-15)
+
+
+def test_rmsnorm_backward_against_autograd_finite_differences_and_loops():
+    import torch
+    T, d, eps = 5, 12, 1e-5
+    h = RNG.normal(size=(T, d))
+    gain = 1.0 + 0.2 * RNG.normal(size=d)
+    dxn = RNG.normal(size=(T, d))
+    dh, dgain = O.rmsnorm_backward(dxn, h, gain, eps)
+    # library autodiff of the library routine
+    th = torch.from_numpy(h).requires_grad_(True)
+    tg = torch.from_numpy(gain).requires_grad_(True)
+    (torch.nn.functional.rms_norm(th, (d,), tg, eps) * torch.from_numpy(dxn)).sum().backward()
+    np.testing.assert_allclose(dh, th.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dgain, tg.grad.numpy(), rtol=1e-11, atol=1e-13)
+    # central differences on L = sum(dxn * xn)
+    loss = lambda hh, gg: float((O.rmsnorm(hh, gg, eps)[0] * dxn).sum())
+    for (t, c) in [(0, 0), (2, 5), (4, 11)]:
+        e = np.zeros_like(h); e[t, c] = 1e-6
+        assert abs((loss(h + e, gain) - loss(h - e, gain)) / 2e-6 - dh[t, c]) < 1e-7
+    for c in (0, 7):
+        e = np.zeros_like(gain); e[c] = 1e-6
+        assert abs((loss(h, gain + e) - loss(h, gain - e)) / 2e-6 - dgain[c]) < 1e-7
+    # dgain by loops
+    rstd = 1.0 / np.sqrt((h * h).mean(axis=1) + eps)
+    for c in (1, 9):
+        assert abs(sum(dxn[t, c] * h[t, c] * rstd[t] for t in range(T)) - dgain[c]) < 1e-12
+    # with unit gain and no eps the output does not depend on the length of h: dh is orthogonal to h
+    dh0, _ = O.rmsnorm_backward(dxn, h, np.ones(d), 0.0)
+    np.testing.assert_allclose((dh0 * h).sum(axis=1), 0.0, atol=1e-13)
+
+
 def test_merge_weighted():
     """Pins: a one-hot weight selects that model; uniform weights 1/N (exact in binary) give the
     mean; small integers come out exactly; np.average (a library routine) agrees when the
