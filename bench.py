@@ -39,6 +39,10 @@ VARIANTS = {
     "switch-cf1.5": dict(name="Switch top-1, router bias +2 on expert 0, capacity factor 1.5", k=1, mode=1,
                          bias=[2.0, 0.0, 0.0, 0.0], tau=1.0, cf=1.5),
     "gumbel": dict(name="Gumbel-softmax sample top-1, tau 0.5", k=1, mode=3, bias=None, tau=0.5, cf=0.0),
+    # the sublayer inside its block: out = h + FF_MoE(rmsnorm(h)); normalisation folded into the router kernel,
+    # residual added in combine, the normalisation's backward (with the residual gradient) as a last stage
+    "norm-block": dict(name="top-2 inside its block (RMSNorm in front, residual add)", k=2, mode=0, bias=None, tau=1.0,
+                       cf=0.0, block=True),
     # 4 FFs split into 8 chunks each (Sec. 3.3 "Splitting Experts"): 32 experts of width 1376, top-8
     "split8-top8": dict(name="32 split experts of width 1376, top-8", k=8, mode=0, bias=None, tau=1.0, cf=0.0, E=32,
                         f=1376),
@@ -109,13 +113,15 @@ def sustained_mfma_tflops(data, ms_target=40.0):
     return flops / (ms * 1e-3) / 1e12
 
 
-def hbm_stages(stage_ms, T, d, E, k, s=2):
+def hbm_stages(stage_ms, T, d, E, k, s=2, block=False):
     """The streaming stages against the 8 TB/s HBM peak: algorithmic bytes per token (bf16 rows of d*s bytes) and
     the rate they were moved at.  route: x read once + indices, gates, probabilities written; combine: k rows read,
     one written; gather_x_bwd: x and dY each read once per routed slot and written once per slot, transposed;
     router_bwd: x read (dW_router), k rows of dxs read and one row of dX written."""
     per_token = {"route": d * s + k * 8 + E * 4, "combine": d * s * (k + 1), "gather_x_bwd": 2 * d * s * 2 * k,
                  "router_bwd": d * s * (k + 2)}
+    if block:   # route also writes the normalised rows; combine also reads the residual; norm_bwd: dXn, h, dY in, dH out
+        per_token.update({"route": 2 * d * s + k * 8 + E * 4 + 4, "combine": d * s * (k + 2), "norm_bwd": 4 * d * s})
     return {n: {"bytes_per_token": b, "ms": stage_ms[n], "tb_per_s": b * T / (stage_ms[n] * 1e-3) / 1e12,
                 "frac_of_hbm_peak": b * T / (stage_ms[n] * 1e-3) / 8e12}
             for n, b in per_token.items() if stage_ms.get(n, 0) > 0}
@@ -221,7 +227,26 @@ def main():
                    lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
+    block = V.get("block", False)
+    if block:   # raw rows of varying length, a gain near one; xn, rstd and dH are allocated here, outside the timing
+        gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 77)
+        h_raw = (L["x"].float() * torch.exp(0.5 * torch.randn((T, 1), generator=gen, device=dev))).to(torch.bfloat16)
+        gain = 1.0 + 0.1 * torch.randn(d, generator=gen, device=dev, dtype=torch.float32)
+        xn, rstd, dH = torch.empty_like(h_raw), torch.empty(T, dtype=torch.float32, device=dev), torch.empty_like(h_raw)
+        dgain = torch.empty(d, dtype=torch.float32, device=dev)
+        ws_bytes = max(ws_bytes, lib.btx_rmsnorm_backward_workspace_bytes(T, d))
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
     def step():
+        if block:
+            B.btx_moe_norm_route(h_raw, gain, 1e-5, L["W_router"], L["b_router"], noise, k, V["mode"],
+                                 B.BTX_LB_TOKEN_FRAC, alpha, out=routing, workspace=ws, xn=xn, rstd=rstd)
+            B.btx_moe_ff_forward(xn, L["W1"], L["W3"], L["W2"], routing, save=True, out=out, saved=saved, workspace=ws,
+                                 residual=h_raw)
+            B.btx_moe_ff_backward(L["dY"], xn, L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
+                                  V["mode"], B.BTX_LB_TOKEN_FRAC, alpha, 1.0, 0, out=grads, workspace=ws)
+            B.btx_rmsnorm_backward(grads.dX, h_raw, gain, rstd, dres=L["dY"], dH=dH, workspace=ws, dgain=dgain)
+            return
         B.btx_moe_route(L["x"], L["W_router"], L["b_router"], noise, k, V["mode"], B.BTX_LB_TOKEN_FRAC, alpha,
                         out=routing, workspace=ws, tau=V["tau"], capacity_factor=V["cf"])
         B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, save=True, out=out, saved=saved, workspace=ws)
@@ -281,7 +306,7 @@ def main():
                          "per_kernel": gemm},
         "stage_ms": stage_ms,
         "step_ms": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},
-        "hbm_stages": hbm_stages(stage_ms, T, d, E, k),
+        "hbm_stages": hbm_stages(stage_ms, T, d, E, k, block=block),
     }
     if args.cpu_sample > 0 and args.variant == "top2":   # the oracle is timed on the benchmark configuration only
         result["cpu_baseline"] = cpu_baseline(L, W, min(args.cpu_sample, T))

@@ -95,7 +95,8 @@ enum {
   BTX_STAGE_DW13 = 9,         /* backward: dW1, dW3                                */
   BTX_STAGE_DW2 = 10,         /* backward: dW2                                     */
   BTX_STAGE_ROUTER_BWD = 11,  /* backward: router gradients and final dX           */
-  BTX_STAGE_COUNT = 12
+  BTX_STAGE_NORM_BWD = 12,    /* btx_rmsnorm_backward: both kernels                */
+  BTX_STAGE_COUNT = 13
 };
 int btx_profile_stages(void** events, int n_pairs);
 
@@ -152,6 +153,51 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
                   float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
                   int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_moe_norm_route - btx_moe_route with the block's pre-normalisation folded into the
+ * router's read of the rows.  The seed model (Sec. 4.1: Llama-2 7B) normalises the residual
+ * stream h before its feed-forward sublayer,
+ *     xn[t,c] = gain[c] * h[t,c] * rstd[t],   rstd[t] = 1 / sqrt(mean_c h[t,c]^2 + eps),
+ * and the block's output is h + FF_MoE(xn): xn is the x of Sec. 3.2, h goes to
+ * btx_moe_ff_forward as `residual`.  One kernel reads h, writes xn (for the expert
+ * GEMMs) and rstd (for the backward pass) and routes on xn.
+ *
+ *   h      [T,d]  x_dtype   raw rows
+ *   gain   [d]    fp32
+ *   eps           >= 0
+ *   xn     [T,d]  x_dtype   out; must not alias h
+ *   rstd   [T]    fp32      out
+ * Mean square, rstd and the product are evaluated in fp64 and xn is rounded once to x_dtype;
+ * the logits are computed from those rounded values, exactly as btx_moe_route would from xn.
+ * Everything else as btx_moe_route (same workspace size).
+ */
+int btx_moe_norm_route(const void* h, int x_dtype, const float* gain, float eps, void* xn, float* rstd,
+                       const float* W_router, const float* b_router, const float* U, int T, int d, int E, int k,
+                       int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
+                       int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_rmsnorm_backward - backward of that normalisation (chain rule; the paper prints no
+ * backward pass).  dXn is the dX that btx_moe_ff_backward returns when it is given xn as x:
+ *     dH[t]    = rstd[t] * gain * dXn[t] - h[t] * rstd[t]^3 * (sum_c gain_c dXn[t,c] h[t,c]) / d  (+ dres[t])
+ *     dgain[c] = sum_t dXn[t,c] * h[t,c] * rstd[t]
+ *
+ *   dXn, h  [T,d]  dtype
+ *   gain    [d]    fp32;  rstd [T] fp32 as written by btx_moe_norm_route
+ *   dres    [T,d]  dtype, may be NULL: added to dH (the gradient that reaches h through the
+ *                  residual connection, i.e. the dY given to btx_moe_ff_backward)
+ *   dH      [T,d]  dtype  out; may alias dXn or dres
+ *   dgain   [d]    fp32   out (overwritten)
+ * fp32 arithmetic, sums in a fixed order (bit-reproducible).
+ * Requirements: d % 8 == 0, d <= 16384; workspace >= btx_rmsnorm_backward_workspace_bytes(T,d).
+ */
+size_t btx_rmsnorm_backward_workspace_bytes(int T, int d);
+int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, const float* rstd, const void* dres,
+                         int dtype, int T, int d, void* dH, float* dgain, void* workspace, size_t workspace_bytes,
+                         void* stream);
 
 /* ---------------------------------------------------------------------------
  * btx_moe_ff_forward - gather tokens into expert groups, the expert SwiGLU

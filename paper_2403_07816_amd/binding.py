@@ -18,7 +18,7 @@ BTX_ROUTE_TOPK_RENORM, BTX_ROUTE_SWITCH_TOP1, BTX_ROUTE_SAMPLE_TOP1, BTX_ROUTE_G
 BTX_LB_TOKEN_FRAC, BTX_LB_GATE_MEAN = 0, 1
 BTX_FLAG_LB_GRAD_THROUGH_U = 1
 STAGE_NAMES = ["route", "gather_x", "up_swiglu", "down", "combine", "gather_dy", "bwd_act", "bwd_dx", "gather_x_bwd",
-               "dw13", "dw2", "router_bwd"]
+               "dw13", "dw2", "router_bwd", "norm_bwd"]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbtx_moe.so")
 _lib = None
@@ -33,6 +33,10 @@ _SIGNATURES = {
     "btx_probe_mfma": (_i, [_vp, _sz, _vp, _i, _i, ctypes.POINTER(ctypes.c_double), _vp]),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
+    "btx_moe_norm_route": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 +
+                           [_vp, _sz, _vp]),
+    "btx_rmsnorm_backward_workspace_bytes": (_sz, [_i, _i]),
+    "btx_rmsnorm_backward": (_i, [_vp] * 5 + [_i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "btx_moe_ff_forward_workspace_bytes": (_sz, [_i] * 6),
     "btx_moe_ff_forward": (_i, [_vp, _vp, _vp, _vp, _i, _i64, _i64, _i, _i, _i, _i, _i] + [_vp] * 4 + [_vp] * 4 +
                            [_vp, _sz, _vp]),
@@ -135,6 +139,49 @@ def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[to
                            _ptr(r.lb_loss), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_route")
     return r
+
+
+def btx_moe_norm_route(h: torch.Tensor, gain: torch.Tensor, eps: float, W_router: torch.Tensor,
+                       b_router: Optional[torch.Tensor] = None, U: Optional[torch.Tensor] = None, k: int = 2,
+                       route_mode: int = BTX_ROUTE_TOPK_RENORM, lb_mode: int = BTX_LB_TOKEN_FRAC, lb_alpha: float = 0.0,
+                       out: Optional[Routing] = None, workspace: Optional[torch.Tensor] = None, tau: float = 1.0,
+                       capacity_factor: float = 0.0, xn: Optional[torch.Tensor] = None,
+                       rstd: Optional[torch.Tensor] = None):
+    """RMS-normalise the rows of h (gain [d] fp32) and route on the result.  Returns (routing, xn, rstd)."""
+    lib = load_library()
+    T, d = h.shape
+    E = W_router.shape[1]
+    assert W_router.shape[0] == d and W_router.dtype == torch.float32
+    assert gain.shape == (d,) and gain.dtype == torch.float32 and h.is_contiguous()
+    r = out if out is not None else alloc_routing(T, E, k, h.device)
+    xn = xn if xn is not None else torch.empty_like(h)
+    rstd = rstd if rstd is not None else torch.empty(T, dtype=torch.float32, device=h.device)
+    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), h.device, workspace)
+    st = lib.btx_moe_norm_route(_ptr(h), _dtype_code(h), _ptr(gain), eps, _ptr(xn), _ptr(rstd), _ptr(W_router),
+                                _ptr(b_router), _ptr(U), T, d, E, k, route_mode, lb_mode, lb_alpha, tau, capacity_factor,
+                                _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts), _ptr(r.offsets),
+                                _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum), _ptr(r.lb_loss),
+                                _ptr(ws), ws.numel(), _stream())
+    _check(st, "btx_moe_norm_route")
+    return r, xn, rstd
+
+
+def btx_rmsnorm_backward(dXn: torch.Tensor, h: torch.Tensor, gain: torch.Tensor, rstd: torch.Tensor,
+                         dres: Optional[torch.Tensor] = None, dH: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, dgain: Optional[torch.Tensor] = None):
+    """Returns (dH [T,d], dgain [d] fp32); dres (e.g. the layer's dY) is added to dH."""
+    lib = load_library()
+    T, d = h.shape
+    assert dXn.shape == h.shape and dXn.dtype == h.dtype and dXn.is_contiguous() and h.is_contiguous()
+    assert gain.dtype == torch.float32 and rstd.dtype == torch.float32 and rstd.numel() == T
+    assert dres is None or (dres.shape == h.shape and dres.dtype == h.dtype and dres.is_contiguous())
+    dH = dH if dH is not None else torch.empty_like(h)
+    dgain = dgain if dgain is not None else torch.empty(d, dtype=torch.float32, device=h.device)
+    ws = _workspace(lib.btx_rmsnorm_backward_workspace_bytes(T, d), h.device, workspace)
+    st = lib.btx_rmsnorm_backward(_ptr(dXn), _ptr(h), _ptr(gain), _ptr(rstd), _ptr(dres), _dtype_code(h), T, d,
+                                  _ptr(dH), _ptr(dgain), _ptr(ws), ws.numel(), _stream())
+    _check(st, "btx_rmsnorm_backward")
+    return dH, dgain
 
 
 def _stacked(W: torch.Tensor) -> Tuple[int, int]:

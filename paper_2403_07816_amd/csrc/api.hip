@@ -113,10 +113,13 @@ size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
   return route_workspace_bytes(T, E, k);
 }
 
-int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T, int d,
-                  int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
-                  int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
-                  float* prob_sum, float* lb_loss, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int route_impl(const void* x, int x_dtype, const float* gain, float eps, void* xn, float* rstd,
+               const float* W_router, const float* b_router, const float* U, int T, int d, int E, int k,
+               int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
+               int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm,
+               int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss, void* workspace,
+               size_t workspace_bytes, void* stream) {
   if (!dtype_ok(x_dtype) || T < 0 || d <= 0 || d % 8 != 0 || E < 1 || E > kMaxExperts || k < 1 || k > E)
     return BTX_ERR_INVALID_ARG;
   if ((int64_t)T * k >= (int64_t)1 << 31) return BTX_ERR_INVALID_ARG;
@@ -136,9 +139,49 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
   const double cap_d = capacity_factor > 0.f ? std::ceil((double)capacity_factor * T * k / E) : 0.0;
   const int cap = cap_d > (double)T * k ? T * k : (int)cap_d;
   RouteArgs a{x, x_dtype, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha, tau, cap, topk_idx, gates, probs,
-              counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace};
+              counts, offsets, perm, inv_pos, gate_sum, prob_sum, lb_loss, workspace, gain, eps, xn, rstd};
   hipStream_t s = static_cast<hipStream_t>(stream);
   BTX_STAGE(BTX_STAGE_ROUTE, launch_route(a, s));
+  return BTX_OK;
+}
+}  // namespace
+
+int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T, int d,
+                  int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
+                  int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum,
+                  float* prob_sum, float* lb_loss, void* workspace, size_t workspace_bytes, void* stream) {
+  return route_impl(x, x_dtype, nullptr, 0.f, nullptr, nullptr, W_router, b_router, U, T, d, E, k, route_mode, lb_mode,
+                    lb_alpha, tau, capacity_factor, topk_idx, gates, probs, counts, offsets, perm, inv_pos, gate_sum,
+                    prob_sum, lb_loss, workspace, workspace_bytes, stream);
+}
+
+int btx_moe_norm_route(const void* h, int x_dtype, const float* gain, float eps, void* xn, float* rstd,
+                       const float* W_router, const float* b_router, const float* U, int T, int d, int E, int k,
+                       int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
+                       int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  if (!(eps >= 0.f)) return BTX_ERR_INVALID_ARG;
+  if (T > 0 && (!gain || !xn || !rstd || xn == h)) return BTX_ERR_INVALID_ARG;
+  return route_impl(h, x_dtype, gain, eps, xn, rstd, W_router, b_router, U, T, d, E, k, route_mode, lb_mode, lb_alpha,
+                    tau, capacity_factor, topk_idx, gates, probs, counts, offsets, perm, inv_pos, gate_sum, prob_sum,
+                    lb_loss, workspace, workspace_bytes, stream);
+}
+
+size_t btx_rmsnorm_backward_workspace_bytes(int T, int d) {
+  if (T <= 0 || d <= 0) return 0;
+  return rmsnorm_bwd_workspace_bytes(T, d);
+}
+
+int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, const float* rstd, const void* dres,
+                         int dtype, int T, int d, void* dH, float* dgain, void* workspace, size_t workspace_bytes,
+                         void* stream) {
+  if (!dtype_ok(dtype) || T < 0 || d <= 0 || d % 8 != 0 || d > 16384) return BTX_ERR_INVALID_ARG;
+  if (T == 0) return BTX_OK;
+  if (!dXn || !h || !gain || !rstd || !dH || !dgain || !workspace) return BTX_ERR_INVALID_ARG;
+  if (workspace_bytes < rmsnorm_bwd_workspace_bytes(T, d)) return BTX_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  BTX_STAGE(BTX_STAGE_NORM_BWD, launch_rmsnorm_bwd(dXn, h, gain, rstd, dres, dtype, T, d, dH, dgain, workspace, s));
   return BTX_OK;
 }
 

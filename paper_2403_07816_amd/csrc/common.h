@@ -71,6 +71,38 @@ constexpr int kDppRor8 = 0x128;   // row_ror:8
 __device__ __forceinline__ float lane_f32(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
+// sum of part[r * ld + i] over r = first, first + step, ... < n: four independent chains so that
+// the loads overlap, combined in a fixed order (the result depends on first, step and n only)
+__device__ __forceinline__ float strided_row_sum(const float* __restrict__ part, size_t ld, size_t i, int first, int step,
+                                                 int n) {
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int r = first;
+  for (; r + 3 * step < n; r += 4 * step) {
+    a0 += part[(size_t)r * ld + i];
+    a1 += part[(size_t)(r + step) * ld + i];
+    a2 += part[(size_t)(r + 2 * step) * ld + i];
+    a3 += part[(size_t)(r + 3 * step) * ld + i];
+  }
+  for (; r < n; r += step) a0 += part[(size_t)r * ld + i];
+  return (a0 + a1) + (a2 + a3);
+}
+
+// fp64 -> bf16 with one rounding: through fp32 first would round twice, which only matters when
+// the fp32 value is an exact bf16 tie; the sign of what the first rounding dropped settles it.
+__device__ __forceinline__ bf16_t f64_to_bf16(double v) {
+  const float q = (float)v;
+  uint32_t u = __float_as_uint(q);
+  if ((u & 0xffffu) == 0x8000u) {
+    const double r = v - (double)q;
+    if (r != 0.0) {
+      const bool up = (r > 0.0) == (q > 0.f);
+      return (bf16_t)((u >> 16) + (up ? 1u : 0u));
+    }
+  }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<kDppXor1>(v);
   v += dpp_f32<kDppXor2>(v);
@@ -121,8 +153,15 @@ struct RouteArgs {
   int32_t* topk_idx; float* gates; float* probs; int32_t* counts; int32_t* offsets; int32_t* perm;
   int32_t* inv_pos; float* gate_sum; float* prob_sum; float* lb_loss;
   void* workspace;
+  // optional RMS normalisation of the rows in front of the router (gain NULL: none): x is then
+  // the raw row, xn [T,d] (x's dtype) receives gain * x * rstd and rstd [T] the row factors
+  const float* gain; float eps; void* xn; float* rstd;
 };
 size_t route_workspace_bytes(int T, int E, int k);
+// backward of the normalisation: dH = d(xn)/d(h)^T dXn (+ dres), dgain[c] = sum_t dXn[t,c] h[t,c] rstd[t]
+size_t rmsnorm_bwd_workspace_bytes(int T, int d);
+int launch_rmsnorm_bwd(const void* dXn, const void* h, const float* gain, const float* rstd, const void* dres,
+                       int dtype, int T, int d, void* dH, float* dgain, void* workspace, hipStream_t s);
 int launch_route(const RouteArgs& a, hipStream_t s);
 
 // rows: dst[r] = src[perm[r] / k]  (k = 1 with perm = NULL copies nothing; perm required)

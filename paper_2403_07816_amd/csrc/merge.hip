@@ -83,22 +83,6 @@ __global__ __launch_bounds__(256) void merge_f32_kernel(Ptrs in, int N, float* _
 // host computes in that order) and rounded once to the storage type.
 struct Weights { float w[kMaxInputs]; };
 
-// fp64 -> bf16, one rounding: through fp32 first would round twice, which only matters when the
-// fp32 value is an exact bf16 tie; the sign of what the first rounding dropped settles that case.
-__device__ __forceinline__ bf16_t f64_to_bf16(double v) {
-  const float q = (float)v;
-  uint32_t u = __float_as_uint(q);
-  if ((u & 0xffffu) == 0x8000u) {
-    const double r = v - (double)q;
-    if (r != 0.0) {
-      const bool up = (r > 0.0) == (q > 0.f);
-      return (bf16_t)((u >> 16) + (up ? 1u : 0u));
-    }
-  }
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-
 __global__ __launch_bounds__(256) void merge_weighted_bf16_kernel(Ptrs in, Weights wt, int N, bf16_t* __restrict__ out,
                                                                    int64_t numel) {
   const int64_t nchunk = numel / 8;

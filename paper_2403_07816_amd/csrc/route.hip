@@ -3,6 +3,10 @@
 // Sec. 3.3 load balancing, Switch and sample-top-1 routing).
 //
 // Three launches, no atomics, no host round trip:
+//   (optional) the RMS normalisation in front of the sublayer (the seed model's blocks
+//   normalise before their feed-forward, Sec. 4.1) is folded into route_tokens: the raw rows
+//   are read once more for their mean square (fp64), the normalised, rounded rows are written
+//   out for the expert GEMMs and are what the logits are computed from.
 //   1. route_tokens   one wavefront handles kTokPerWave tokens at a time: fp32 dot
 //                     products of the token row with W_router (lanes split the row,
 //                     butterfly reduction), then softmax / selection / gates with one
@@ -40,6 +44,32 @@ template <> struct RowLoad<float> {
   }
 };
 
+// normalised value, rounded once to the row's storage type; `back` is that value again as float
+template <typename XT> struct NormRound;
+template <> struct NormRound<bf16_t> {
+  static __device__ __forceinline__ bf16_t rnd(double v, float& back) {
+    const bf16_t h = f64_to_bf16(v);
+    back = bf16_to_f32(h);
+    return h;
+  }
+  static __device__ __forceinline__ void st8(bf16_t* p, const bf16_t* h) {
+    *reinterpret_cast<u32x4*>(p) = u32x4{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
+                                         (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
+  }
+};
+template <> struct NormRound<float> {
+  static __device__ __forceinline__ float rnd(double v, float& back) { return back = (float)v; }
+  static __device__ __forceinline__ void st8(float* p, const float* h) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{h[0], h[1], h[2], h[3]};
+    *reinterpret_cast<f32x4*>(p + 4) = f32x4{h[4], h[5], h[6], h[7]};
+  }
+};
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);   // every lane ends with the same bits
+  return v;
+}
+
 struct Best { float v; int i; };
 // larger value wins; equal values: lower index wins
 __device__ __forceinline__ Best best_of(Best a, Best b) {
@@ -70,18 +100,41 @@ __device__ __forceinline__ float wave_incl_scan(float v, int lane) {
 
 // EC experts are accumulated per pass over the row; kTokPerWave tokens share each
 // W_router load.
-template <typename XT, int EC>
+template <typename XT, int EC, bool NORM>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
     const XT* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ br,
     const float* __restrict__ U, int T, int d, int E, int k, int mode, float inv_tau, int32_t* __restrict__ topk_idx,
     float* __restrict__ gates, float* __restrict__ probs, int32_t* __restrict__ blk_counts,
-    float* __restrict__ blk_gsum, float* __restrict__ blk_psum) {
+    float* __restrict__ blk_gsum, float* __restrict__ blk_psum, const float* __restrict__ gain, float eps,
+    XT* __restrict__ xn, float* __restrict__ rstd_out) {
   __shared__ float s_logit[kWavesPerBlock][kTokPerWave][kMaxExperts];
   __shared__ float s_stat[kWavesPerBlock][3][kMaxExperts];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int t0 = blockIdx.x * kTokPerBlock + wave * kTokPerWave;
   const bool vec4 = (E % EC) == 0 && (E % 4) == 0;
+
+  // ---- row factors of the normalisation -------------------------------------
+  // fp64 throughout: the rounded rows then agree with a host fp64 evaluation except where the
+  // exact value lies within 1e-16 (relative) of a rounding tie, and so do the routing decisions.
+  double rs[kTokPerWave];
+  if (NORM) {
+    double ss[kTokPerWave] = {};
+    for (int c0 = lane * 8; c0 < d; c0 += kWave * 8) {
+#pragma unroll
+      for (int q = 0; q < kTokPerWave; ++q) {
+        float v[8];
+        RowLoad<XT>::ld8(x + (size_t)min(t0 + q, T - 1) * d + c0, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss[q] += (double)v[i] * (double)v[i];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kTokPerWave; ++q) {
+      rs[q] = 1.0 / sqrt(wave_sum_f64(ss[q]) / (double)d + (double)eps);
+      if (lane == 0 && t0 + q < T) rstd_out[t0 + q] = (float)rs[q];
+    }
+  }
 
   // ---- logits -------------------------------------------------------------
   for (int e0 = 0; e0 < E; e0 += EC) {
@@ -96,6 +149,17 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
       for (int q = 0; q < kTokPerWave; ++q) {
         const int t = min(t0 + q, T - 1);  // clamped rows are computed and then dropped
         RowLoad<XT>::ld8(x + (size_t)t * d + c0, xv[q]);
+      }
+      if (NORM) {
+        float gv[8];
+        RowLoad<float>::ld8(gain + c0, gv);
+#pragma unroll
+        for (int q = 0; q < kTokPerWave; ++q) {
+          XT h[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) h[i] = NormRound<XT>::rnd((double)xv[q][i] * rs[q] * (double)gv[i], xv[q][i]);
+          if (e0 == 0 && t0 + q < T) NormRound<XT>::st8(xn + (size_t)(t0 + q) * d + c0, h);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -329,9 +393,17 @@ template <typename XT>
 void launch_tokens(const RouteArgs& a, int nblk, int32_t* bc, float* bg, float* bp, hipStream_t s) {
   const XT* x = static_cast<const XT*>(a.x);
   dim3 grid(nblk), block(kWavesPerBlock * kWave);
-#define BTX_ROUTE_LAUNCH(EC)                                                                                  \
-  route_tokens_kernel<XT, EC><<<grid, block, 0, s>>>(x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k,      \
-                                                      a.route_mode, 1.f / a.tau, a.topk_idx, a.gates, a.probs, bc, bg, bp)
+#define BTX_ROUTE_LAUNCH(EC)                                                                                       \
+  do {                                                                                                             \
+    if (a.gain)                                                                                                    \
+      route_tokens_kernel<XT, EC, true><<<grid, block, 0, s>>>(                                                    \
+          x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates,       \
+          a.probs, bc, bg, bp, a.gain, a.eps, static_cast<XT*>(a.xn), a.rstd);                                      \
+    else                                                                                                           \
+      route_tokens_kernel<XT, EC, false><<<grid, block, 0, s>>>(                                                   \
+          x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates,       \
+          a.probs, bc, bg, bp, nullptr, 0.f, nullptr, nullptr);                                                     \
+  } while (0)
   if (a.E <= 1) BTX_ROUTE_LAUNCH(1);
   else if (a.E <= 2) BTX_ROUTE_LAUNCH(2);
   else if (a.E <= 4) BTX_ROUTE_LAUNCH(4);

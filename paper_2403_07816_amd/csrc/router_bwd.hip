@@ -149,20 +149,24 @@ __global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__
   }
 }
 
-// 64 outputs per block; 4 thread groups each add every 4th partial, then the 4 sums are added
+// 64 outputs per block; 16 thread groups each add every 16th partial, then the 16 sums are added
 // in group order (a fixed order, like everything else here).
-__global__ __launch_bounds__(256) void dwr_reduce_kernel(const float* __restrict__ part, const float* __restrict__ db_part,
-                                                         int nchunk, int dE, int E, float* __restrict__ dWr,
-                                                         float* __restrict__ db) {
-  __shared__ float s_sum[4][64];
+constexpr int kRedGroups = 16;
+__global__ __launch_bounds__(64 * kRedGroups) void dwr_reduce_kernel(const float* __restrict__ part,
+                                                                      const float* __restrict__ db_part, int nchunk,
+                                                                      int dE, int E, float* __restrict__ dWr,
+                                                                      float* __restrict__ db) {
+  __shared__ float s_sum[kRedGroups][64];
   const int o = threadIdx.x % 64, grp = threadIdx.x / 64;
   const int i = blockIdx.x * 64 + o;
-  float a = 0.f;
-  if (i < dE)
-    for (int c = grp; c < nchunk; c += 4) a += part[(size_t)c * dE + i];
-  s_sum[grp][o] = a;
+  s_sum[grp][o] = i < dE ? strided_row_sum(part, dE, i, grp, kRedGroups, nchunk) : 0.f;
   __syncthreads();
-  if (grp == 0 && i < dE) dWr[i] = (s_sum[0][o] + s_sum[1][o]) + (s_sum[2][o] + s_sum[3][o]);
+  if (grp == 0 && i < dE) {
+    float a = 0.f;
+#pragma unroll
+    for (int g = 0; g < kRedGroups; ++g) a += s_sum[g][o];
+    dWr[i] = a;
+  }
   if (db && blockIdx.x == 0 && threadIdx.x < E) {
     float b = 0.f;
     for (int c = 0; c < nchunk; ++c) b += db_part[(size_t)c * E + threadIdx.x];
@@ -269,8 +273,8 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
   else
     dwr_partial_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(a.x), ds, a.T, a.d, a.E, part, dbp);
   BTX_LAUNCH_CHECK();
-  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 64), 256, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E, a.E,
-                                                                     a.dW_router, a.db_router);
+  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 64), 64 * kRedGroups, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E,
+                                                                                 a.E, a.dW_router, a.db_router);
   BTX_LAUNCH_CHECK();
   const dim3 dx_grid(ceil_div(a.T, kDxTok), ceil_div(a.d, 4 * kWave * 8));
   auto dx_launch = [&](auto tag) {

@@ -160,3 +160,51 @@ def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
             else:
                 assert_close(got[e], want, tol, f"{name}[{e}]")
     return G, r, out, g
+
+
+def run_block_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_mode=B.BTX_LB_TOKEN_FRAC, alpha=0.01,
+                        bias=None, eps=1e-5, seed=synth.BASE_SEED, cf=0.0):
+    """The sublayer inside its block: out = h + FF_MoE(rmsnorm(h)), forward and backward, with the
+    normalisation folded into the router kernel and its backward as a kernel of its own."""
+    L = synth.make_layer(T, d, f, E, dtype=dtype, seed=seed, router_bias=bias, with_dY=True,
+                         with_U=(mode == B.BTX_ROUTE_SAMPLE_TOP1), with_gumbel=(mode == B.BTX_ROUTE_GUMBEL_TOP1))
+    gen = torch.Generator().manual_seed(seed + 77)
+    scale = torch.exp(0.5 * torch.randn((T, 1), generator=gen))              # rows of different length
+    h = (L["x"].float() * scale).to(dtype)
+    gain = (1.0 + 0.1 * torch.randn(d, generator=gen)).float()
+    G = to_dev(L)
+    hg, gg = h.cuda(), gain.cuda()
+    tol = TOL[dtype]
+
+    r, xn, rstd = B.btx_moe_norm_route(hg, gg, eps, G["W_router"], G["b_router"], G["U"], k, mode, lb_mode, alpha,
+                                       capacity_factor=cf)
+    xn_o, rstd_o = O.rmsnorm(to_np(h), to_np(gain), eps)
+    np.testing.assert_allclose(to_np(rstd), rstd_o, rtol=1e-6)
+    if dtype == torch.bfloat16:
+        assert np.array_equal(to_np(xn), O.round_to_bf16(xn_o).astype(np.float64)), "normalised rows differ"
+    else:
+        np.testing.assert_allclose(to_np(xn), xn_o, rtol=2e-7, atol=0)
+    # from here on the oracle takes the rounded rows the GPU wrote (for bf16: its own, bit for bit)
+    Lx = dict(L)
+    Lx["x"] = xn.cpu()
+    fwd = check_route(r, Lx, k, mode, alpha, lb_mode, cf=cf)
+    out, h1, h3 = B.btx_moe_ff_forward(xn, G["W1"], G["W3"], G["W2"], r, save=True, residual=hg)
+    assert_close(to_np(out), fwd["out"] + to_np(h), tol, "block out")
+    g = B.btx_moe_ff_backward(G["dY"], xn, G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, mode, lb_mode, alpha,
+                              1.0, 0, noise=G["U"] if mode == B.BTX_ROUTE_GUMBEL_TOP1 else None)
+    ref = O.moe_backward(to_np(Lx["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
+                         experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["dY"]), fwd, alpha, lb_mode, 1.0,
+                         False)
+    assert_close(to_np(g.dX), ref["dX"], tol, "dXn")
+    dH, dgain = B.btx_rmsnorm_backward(g.dX, hg, gg, rstd, dres=G["dY"])
+    dh_o, dgain_o = O.rmsnorm_backward(ref["dX"], to_np(h), to_np(gain), eps)
+    assert_close(to_np(dH), dh_o + to_np(L["dY"]), tol, "dH")
+    assert_close(to_np(dgain), dgain_o, tol, "dgain")
+    # in place, and without the residual gradient
+    dH2, dgain2 = B.btx_rmsnorm_backward(g.dX, hg, gg, rstd)
+    assert_close(to_np(dH2), dh_o, tol, "dH without residual")
+    dx_copy = g.dX.clone()
+    B.btx_rmsnorm_backward(dx_copy, hg, gg, rstd, dres=G["dY"], dH=dx_copy)
+    assert torch.equal(dx_copy, dH), "in-place dH differs"
+    assert torch.equal(dgain2, dgain)
+    return r, xn, rstd

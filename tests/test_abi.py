@@ -118,6 +118,39 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     assert lib.btx_merge_weighted(arr, wts, 2, p, -1, 0, null) == 1
 
 
+def test_norm_route_and_norm_backward_reject_bad_arguments(lib):
+    p, null = ctypes.c_void_p(256), ctypes.c_void_p(0)
+    q = ctypes.c_void_p(512)
+
+    def nr(h=p, gain=p, eps=1e-5, xn=q, rstd=p, T=4, d=64, E=4, k=2, ws=1 << 20):
+        return lib.btx_moe_norm_route(h, 0, gain, eps, xn, rstd, p, null, null, T, d, E, k, 0, 0, 0.0, 1.0, 0.0,
+                                      p, p, p, p, p, p, p, p, p, p, p, ws, null)
+    assert nr(gain=null) == 1
+    assert nr(xn=null) == 1
+    assert nr(rstd=null) == 1
+    assert nr(xn=p) == 1                    # xn must not alias h
+    assert nr(eps=-1.0) == 1
+    assert nr(d=60) == 1
+    assert nr(k=5) == 1
+    assert nr(ws=0) == 3
+    assert nr(T=0) == 0
+
+    def nb(dxn=p, h=p, gain=p, rstd=p, dres=null, dt=0, T=4, d=64, dH=q, dgain=p, ws=1 << 20):
+        return lib.btx_rmsnorm_backward(dxn, h, gain, rstd, dres, dt, T, d, dH, dgain, p, ws, null)
+    assert nb(dxn=null) == 1
+    assert nb(gain=null) == 1
+    assert nb(rstd=null) == 1
+    assert nb(dH=null) == 1
+    assert nb(dgain=null) == 1
+    assert nb(dt=7) == 1
+    assert nb(d=60) == 1
+    assert nb(d=16392) == 1
+    assert nb(ws=0) == 3
+    assert nb(T=0) == 0
+    assert lib.btx_rmsnorm_backward_workspace_bytes(16384, 4096) == 1024 * 4096 * 4
+    assert lib.btx_rmsnorm_backward_workspace_bytes(0, 4096) == 0
+
+
 def test_mix_experts_rejects_bad_arguments(lib):
     bad = 1
     a, b, c, x, y, z = (ctypes.c_void_p(0x1000 * i) for i in range(1, 7))

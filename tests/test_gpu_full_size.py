@@ -109,6 +109,32 @@ def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True
     return r, out, g, fwd
 
 
+def test_config2_block_rmsnorm_route_and_norm_backward_every_row(big):
+    """The block's normalisation at the benchmark's size, checked on every row: the normalised
+    rows against the oracle bit for bit, the routing against btx_moe_route on those rows, and the
+    normalisation's backward (with the residual gradient) against the oracle."""
+    gen = torch.Generator(device="cuda").manual_seed(99)
+    h = (big["x"].float() * torch.exp(0.5 * torch.randn((T_FULL, 1), generator=gen, device="cuda"))).to(BF16)
+    gain = 1.0 + 0.1 * torch.randn(D, generator=gen, device="cuda", dtype=torch.float32)
+    r, xn, rstd = B.btx_moe_norm_route(h, gain, 1e-5, big["W_router"], k=2, lb_alpha=0.01)
+    xn_o, rstd_o = O.rmsnorm(f32(h).astype(np.float64), f32(gain).astype(np.float64), 1e-5)
+    assert np.array_equal(f32(xn), O.round_to_bf16(xn_o))
+    np.testing.assert_allclose(f32(rstd), rstd_o, rtol=1e-6)
+    del xn_o
+    r2 = B.btx_moe_route(xn, big["W_router"], k=2, lb_alpha=0.01)
+    for name in ("topk_idx", "gates", "probs", "counts", "offsets", "perm", "inv_pos", "gate_sum", "prob_sum", "lb_loss"):
+        assert torch.equal(getattr(r, name), getattr(r2, name)), name
+    dXn = big["dY"]                                        # any gradient of the right shape and scale
+    dres = torch.roll(big["dY"], 1, dims=0).contiguous()
+    dH, dgain = B.btx_rmsnorm_backward(dXn, h, gain, rstd, dres=dres)
+    dh_o, dgain_o = O.rmsnorm_backward(f32(dXn).astype(np.float64), f32(h).astype(np.float64),
+                                       f32(gain).astype(np.float64), 1e-5)
+    assert_close(f32(dH), dh_o + f32(dres), TOL[BF16], "dH")
+    assert_close(f32(dgain), dgain_o, TOL[BF16], "dgain")
+    again = B.btx_rmsnorm_backward(dXn, h, gain, rstd, dres=dres)
+    assert torch.equal(again[0], dH) and torch.equal(again[1], dgain)
+
+
 def test_config1_forward_T4096(big):
     run_full(big, 4096, 2, B.BTX_ROUTE_TOPK_RENORM, 0.0, 0.0, big["W1"], big["W3"], big["W2"], big["W_router"],
              backward=False)

@@ -9,7 +9,7 @@ from paper_2403_07816_amd import binding as B
 from paper_2403_07816_amd import synth
 
 from conftest import assert_close
-from helpers import TOL, run_layer_and_check, to_dev, to_np, experts_np, check_route
+from helpers import TOL, run_block_and_check, run_layer_and_check, to_dev, to_np, experts_np, check_route
 
 pytestmark = pytest.mark.gpu
 
@@ -234,6 +234,34 @@ def test_bf16_top2_with_capacity_factor():
 
 def test_bf16_expert_without_tokens():
     run_layer_and_check(300, 128, 256, 4, 2, BF16, bias=[0, -60.0, 0, 0], unit_rms=True)
+
+
+# ------------------------------------------------- the sublayer in its block
+@pytest.mark.parametrize("T,d,f,E,k,dtype", [
+    (300, 64, 176, 4, 2, F32),          # fp32, ragged last token block
+    (77, 2056, 64, 3, 1, F32),          # d not a multiple of the 2048-column thread stride, E < 4
+    (1000, 512, 1376, 8, 2, BF16),      # MFMA path
+    (515, 4096, 256, 4, 2, BF16),       # the benchmark's d
+    (130, 4608, 128, 16, 4, BF16),      # E > 8: several expert passes over the rows; d > 4096
+])
+def test_block_rmsnorm_route_forward_backward(T, d, f, E, k, dtype):
+    run_block_and_check(T, d, f, E, k, dtype)
+
+
+def test_block_rmsnorm_with_switch_routing_and_capacity():
+    run_block_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_SWITCH_TOP1, bias=[2.0, 0, 0, 0], cf=1.5)
+
+
+def test_block_rmsnorm_route_matches_plain_route_on_the_normalised_rows():
+    """The fused kernel must route exactly as btx_moe_route does when handed the rows it wrote."""
+    L = synth.make_layer(700, 512, 64, 8, dtype=BF16)
+    h = (L["x"].float() * 3.0).to(BF16).cuda()
+    gain = torch.linspace(0.5, 1.5, 512).cuda()
+    Wr = L["W_router"].cuda()
+    r1, xn, _ = B.btx_moe_norm_route(h, gain, 1e-5, Wr, k=2, lb_alpha=0.01)
+    r2 = B.btx_moe_route(xn, Wr, k=2, lb_alpha=0.01)
+    for name in ("topk_idx", "gates", "probs", "counts", "offsets", "perm", "inv_pos", "gate_sum", "prob_sum", "lb_loss"):
+        assert torch.equal(getattr(r1, name), getattr(r2, name)), name
 
 
 # ---------------------------------------------------------------------- merge
