@@ -388,6 +388,54 @@ def test_layer_step_replays_from_a_hip_graph():
             assert torch.equal(got, ref)
 
 
+def test_block_step_replays_from_a_hip_graph():
+    """The same for the sublayer inside its block: norm + route, forward with the residual,
+    backward, normalisation backward in place on dX."""
+    T, d, f, E, k = 600, 256, 384, 4, 2
+    L = to_dev(synth.make_layer(T, d, f, E, dtype=BF16, with_dY=True))
+    h = (L["x"].float() * 2.5).to(BF16)
+    gain = torch.linspace(0.8, 1.2, d, device="cuda")
+    lib = B.load_library()
+    routing = B.alloc_routing(T, E, k, "cuda")
+    xn, rstd, out = torch.empty_like(h), torch.empty(T, device="cuda"), torch.empty_like(h)
+    dgain = torch.empty(d, device="cuda")
+    saved = (torch.empty((T * k, f), dtype=BF16, device="cuda"), torch.empty((T * k, f), dtype=BF16, device="cuda"))
+    grads = B.Grads(torch.empty_like(h), torch.empty((d, E), device="cuda"), torch.empty(E, device="cuda"),
+                    torch.empty_like(L["W1"]), torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
+    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, E, k),
+                         lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
+                         lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
+                         lib.btx_rmsnorm_backward_workspace_bytes(T, d)), dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.btx_moe_norm_route(h, gain, 1e-5, L["W_router"], None, None, k, lb_alpha=0.01, out=routing, workspace=ws,
+                             xn=xn, rstd=rstd)
+        B.btx_moe_ff_forward(xn, L["W1"], L["W3"], L["W2"], routing, out=out, saved=saved, workspace=ws, residual=h)
+        B.btx_moe_ff_backward(L["dY"], xn, L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
+                              lb_alpha=0.01, lb_grad_scale=1.0, out=grads, workspace=ws)
+        B.btx_rmsnorm_backward(grads.dX, h, gain, rstd, dres=L["dY"], dH=grads.dX, workspace=ws, dgain=dgain)
+
+    step()
+    torch.cuda.synchronize()
+    watched = (xn, out, grads.dX, dgain, grads.dW3, routing.inv_pos)
+    want = [t.clone() for t in watched]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        for t in (xn, out, grads.dX, dgain, grads.dW3):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(watched, want):
+            assert torch.equal(got, ref)
+
+
 # -------------------------------------------------------------------- AdamW
 @pytest.mark.parametrize("gdtype", [F32, BF16])
 @pytest.mark.parametrize("n", [4096 * 33 + 3, 5, 1 << 20])
