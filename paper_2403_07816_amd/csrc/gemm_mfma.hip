@@ -19,8 +19,9 @@
 //     memory, [BK][cols], and read with the transposing ds_read_b64_tr_b16; x and dY reach the
 //     dW products already transposed and zero-padded per expert.  The swizzles are applied by choosing which
 //     global chunk each lane fetches, since a direct copy fixes the LDS position per lane;
-//   * v_mfma_f32_32x32x16_bf16 with the roles of the operands swapped (the N-side fragment is
-//     passed first), so that each lane ends up with 4 consecutive output columns of one row
+//   * v_mfma_f32_16x16x32_bf16 (on this chip it sustains a seventh more than the 32x32x16 form
+//     under the same power limit) with the roles of the operands swapped (the N-side fragment
+//     is passed first), so that each lane ends up with 4 consecutive output columns of one row
 //     and stores 8 bytes at a time;
 //   * grouped rows: tiles are enumerated per expert on the device (no host sync); a tile past
 //     the last one exits.  Rows beyond a group's end are loaded from a clamped address and
@@ -28,6 +29,7 @@
 //     at valid data and the A fragments of its empty half zeroed in registers.
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
+#include <type_traits>
 
 #ifndef BTX_SUP_M
 #define BTX_SUP_M 16   // default supertile: row tiles x column tiles that run concurrently chip-wide
@@ -110,25 +112,27 @@ struct Gemm {
   static constexpr bool DUAL = (MODE == UP || MODE == DW13);
   static constexpr bool GROUP_K = (MODE == DW13 || MODE == DW2);
   static constexpr int NW = WM * WN, NT = NW * kWave;
-  static constexpr int TM = BM / WM / 32;                      // 32-row fragments per wavefront
-  static constexpr int TN = BN / WN / 32;
+  static constexpr int TM = BM / WM / 16;                      // 16-row fragments per wavefront
+  static constexpr int TN = BN / WN / 16;
   static constexpr int TNH = DUAL ? TN / 2 : TN;
   static constexpr int BNH = DUAL ? BN / 2 : BN;               // output columns per B panel
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
   // LDS: NSA = 3 stages of the A tile, then NSB = 2 stages of the B tile (the ping-pong schedule)
   static constexpr int B_BASE = NSA * A_BYTES;
   static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
-  static_assert(NSA == 3 && NSB == 2 && WM * WN == 8 && BK == 64, "the schedule is written for 8 wavefronts, 4 k steps");
+  static_assert(NSA == 3 && NSB == 2 && WM * WN == 8 && BK == 64, "the schedule is written for 8 wavefronts, 2 k steps");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   static constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;  // per wavefront per tile
-  static constexpr int KSTEPS = BK / 16;
+  static constexpr int KSTEPS = BK / 32;                       // k steps (one MFMA deep) per tile
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split into 1 KB wave copies");
-  static_assert(TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "bad wave tiling");
+  static_assert(TM >= 2 && TM % 2 == 0 && TN >= 1 && (!DUAL || TN % 2 == 0), "bad wave tiling");
 
   // ---- LDS addressing ----------------------------------------------------
   // K-contiguous tile: [rows][BK], 16-byte chunks XOR-swizzled by row
   static __device__ __forceinline__ int kc_swz(int row) { return (row >> 1) & 7; }
-  // strided-K tile: [BK][COLS], 16-byte chunk index XORed with (k & 3) << 2
+  // strided-K tile: [BK][COLS], 16-byte chunk index XORed with tr_swz(k): bits 2-3 keep the four
+  // k rows of one transposing read apart, bit 1 the two 16-lane groups that share a pass
+  static __device__ __forceinline__ int tr_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 
   // byte offset inside a wave's copy `seg` (1 KB each) -> global element offset, for both layouts
   template <bool KC, int ROWS_OR_COLS>
@@ -144,21 +148,24 @@ struct Gemm {
       const int k = o / PITCH;
       const int phys = (o % PITCH) / 16;
       major = k;                                // k row of the tile
-      minor_elem = (phys ^ ((k & 3) << 2)) * 8; // column offset inside the tile
+      minor_elem = (phys ^ tr_swz(k)) * 8;      // column offset inside the tile
     }
   }
 
+  // fragment of 16 rows x 32 k: lane l holds row l % 16, k = 32 ks + 8 (l / 16) .. + 7
   static __device__ __forceinline__ bf16x8 read_kc(const char* tile, int row, int ks, int lane) {
-    const int r = row + (lane & 31);
-    const int chunk = 2 * ks + (lane >> 5);
+    const int r = row + (lane & 15);
+    const int chunk = 4 * ks + (lane >> 4);
     return *reinterpret_cast<const bf16x8*>(tile + r * (BK * 2) + ((chunk ^ kc_swz(r)) << 4));
   }
   template <int COLS>
   static __device__ __forceinline__ bf16x8 read_tr(const char* tile, int col, int ks, int lane) {
+    // a transposing read hands lane 4a+b of a 16-lane group element b of what lanes a, a+4, a+8,
+    // a+12 fetched (4 consecutive columns each): lane r fetches k row r/4 at columns 4 (r%4) ..
     const int g = lane >> 4, r = lane & 15;
-    const int k = 16 * ks + 8 * (g >> 1) + (r >> 2);
-    const int c = col + 16 * (g & 1) + 4 * (r & 3);
-    const int off = k * (COLS * 2) + ((((c >> 3) ^ ((r >> 2) << 2)) << 4) | ((c & 7) << 1));
+    const int k = 32 * ks + 8 * g + (r >> 2);
+    const int c = col + 4 * (r & 3);
+    const int off = k * (COLS * 2) + ((((c >> 3) ^ tr_swz(k)) << 4) | ((c & 7) << 1));
     typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(tile + off));
     const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(tile + off + 4 * COLS * 2));
@@ -334,25 +341,25 @@ struct Gemm {
       }
     };
 
-    f32x16 acc[TM][TN];
+    f32x4 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
     auto load_frags = [&](int kt, int ks, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
       const char* At = smem + (kt % NSA) * A_BYTES;
       const char* Bt = smem + B_BASE + (kt % NSB) * B_BYTES;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const int r = wm * (TM * 32) + i * 32;
+        const int r = wm * (TM * 16) + i * 16;
         af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int c = wn * (TNH * 32) + (j % TNH) * 32;
+        const int c = wn * (TNH * 16) + (j % TNH) * 16;
         bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
       }
     };
@@ -361,14 +368,14 @@ struct Gemm {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     };
     // grouped-K: the k rows past an expert's last one meet the zero fill of the transposed operand
 
     {
       // Ping-pong schedule.  The two wavefronts that share a SIMD (w and w+4) alternate
       // between a memory phase (LDS fragment reads of half a tile + a quarter of the copies
-      // of a later tile) and a compute phase (an uninterrupted run of 16 MFMAs), half a period
+      // of a later tile) and a compute phase (an uninterrupted run of 32 MFMAs), half a period
       // apart and kept in step by a barrier at every phase boundary.  The matrix pipe always
       // has one wavefront feeding it and is never held up behind a wavefront that is stuck
       // issuing copies or waiting for LDS.  Time is counted in phases; tile kt occupies phases
@@ -425,23 +432,31 @@ struct Gemm {
     }
 
     // ---- epilogue ----------------------------------------------------------
-    // acc[i][j][v]: row m = row0 + wm*TM*32 + i*32 + lane%32,
-    //               col n = col0 + wn*TNH*32 + (j%TNH)*32 + 8*(v/4) + 4*(lane/32) + v%4
-    // In that layout one store instruction would touch 32 rows with 16 bytes each.  Instead
+    // acc[i][j][v]: row m = row0 + wm*TM*16 + i*16 + lane%16,
+    //               col n = col0 + wn*TNH*16 + (j%TNH)*16 + 4*(lane/16) + v
+    // In that layout one store instruction would touch 16 rows with 8 to 16 bytes each.  Instead
     // every wavefront turns its results around in a private piece of LDS, one band of 32 rows
-    // at a time: the lanes write their 4-column pieces, read the band back as 16-byte chunks
-    // that follow each other along a row, and store whole row segments (64 to 256 contiguous
-    // bytes per row).  BWD_ACT fetches the saved h1/h3 band the same way round.  The operand
-    // stages are dead by now: in the ping-pong schedule the barrier that ends group 0's last
-    // compute phase comes after group 1's last fragment read and after every copy has landed.
-    const int lane_m = lane & 31, lane_h = lane >> 5;
-    const int wcol0 = col0 + wn * (TNH * 32);         // first output column of this wavefront (per panel)
+    // (two fragment rows) at a time: the lanes write their 4-column pieces, read the band back
+    // as 16-byte chunks that follow each other along a row, and store whole row segments (64 to
+    // 256 contiguous bytes per row).  BWD_ACT fetches the saved h1/h3 band the same way round.
+    // The operand stages are dead by now: in the ping-pong schedule the barrier that ends group
+    // 0's last compute phase comes after group 1's last fragment read and after every copy has
+    // landed.
+    const int lane_m = lane & 15, lane_c = lane >> 4;
+    const int wcol0 = col0 + wn * (TNH * 16);         // first output column of this wavefront (per panel)
+    constexpr int NB = TM / 2;                         // 32-row bands per wavefront
+    // byte offset, inside a band, of this lane's 4-column piece of fragment (i2, j); ES = element size
+    auto piece = [&](auto rowb_tag, auto es_tag, int i2, int j) {
+      constexpr int ROWB = decltype(rowb_tag)::value, ES = decltype(es_tag)::value;
+      const int byte = (j * 16 + 4 * lane_c) * ES;
+      return stage_off<ROWB, 4 * ES>(i2 * 16 + lane_m, byte >> 4) + (byte & 15);
+    };
     float dg_acc[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) dg_acc[i] = 0.f;
 
     if constexpr (MODE == BWD_ACT) {
-      constexpr int ROWB = TNH * 64;                  // bytes per band row
+      constexpr int ROWB = TNH * 32;                  // bytes per band row
       constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
       static_assert(3 * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
       char* bufA = smem + wave * (3 * 32 * ROWB);
@@ -450,36 +465,39 @@ struct Gemm {
       const int cr = lane / CPR, cc = lane % CPR;     // row (per pass) and chunk of the row-contiguous view
       const int cn = wcol0 + cc * 8;
       u32x4 p1[NI], p3[NI];
-      float gate_next;
-      // band i of h1/h3 in the row-contiguous view (clamped, always valid addresses)
-      auto fetch = [&](int i) {
-        const int mb = row0 + wm * (TM * 32) + i * 32;
+      float gate_next[2];
+      // band ib of h1/h3 in the row-contiguous view (clamped, always valid addresses)
+      auto fetch = [&](int ib) {
+        const int mb = row0 + wm * (TM * 16) + ib * 32;
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
           const size_t idx = (size_t)min(mb + t * RPI + cr, row_end - 1) * g.ldc + min(cn, g.N - 8);
           p1[t] = *reinterpret_cast<const u32x4*>(g.H1 + idx);
           p3[t] = *reinterpret_cast<const u32x4*>(g.H3 + idx);
         }
-        gate_next = g.gates[g.perm[min(mb + lane_m, row_end - 1)]];
+#pragma unroll
+        for (int i2 = 0; i2 < 2; ++i2) gate_next[i2] = g.gates[g.perm[min(mb + i2 * 16 + lane_m, row_end - 1)]];
       };
       fetch(0);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int mb = row0 + wm * (TM * 32) + i * 32;
+      for (int ib = 0; ib < NB; ++ib) {
+        const int mb = row0 + wm * (TM * 16) + ib * 32;
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
           const uint32_t o = stage_off<ROWB, 8>(t * RPI + cr, cc);
           *reinterpret_cast<u32x4*>(bufA + o) = p1[t];
           *reinterpret_cast<u32x4*>(bufB + o) = p3[t];
         }
-        const float gate = gate_next;
-        if (i + 1 < TM) fetch(i + 1);                 // in flight during the arithmetic below
-        const bool m_ok = mb + lane_m < row_end;
+        const float gate2[2] = {gate_next[0], gate_next[1]};
+        if (ib + 1 < NB) fetch(ib + 1);               // in flight during the arithmetic below
 #pragma unroll
-        for (int j = 0; j < TNH; ++j)
+        for (int i2 = 0; i2 < 2; ++i2) {
+          const int i = 2 * ib + i2;
+          const float gate = gate2[i2];
+          const bool m_ok = mb + i2 * 16 + lane_m < row_end;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const uint32_t o = stage_off<ROWB, 8>(lane_m, 4 * j + q) + 8 * lane_h;
+          for (int j = 0; j < TNH; ++j) {
+            const uint32_t o = piece(std::integral_constant<int, ROWB>{}, std::integral_constant<int, 2>{}, i2, j);
             const u32x2 a1 = *reinterpret_cast<const u32x2*>(bufA + o);
             const u32x2 a3 = *reinterpret_cast<const u32x2*>(bufB + o);
             const float z[4] = {bf16lo(a1[0]), bf16hi(a1[0]), bf16lo(a1[1]), bf16hi(a1[1])};
@@ -487,7 +505,7 @@ struct Gemm {
             float o1[4], o3[4], oa[4], dot = 0.f;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-              const float dd = acc[i][j][4 * q + x];
+              const float dd = acc[i][j][x];
               const float sg = sigmoid_f(z[x]), sl = z[x] * sg;
               const float a = sl * v3[x];
               dot = fmaf(dd, a, dot);
@@ -496,12 +514,13 @@ struct Gemm {
               o3[x] = da * sl;
               oa[x] = gate * a;
             }
-            if (m_ok && wcol0 + j * 32 + 8 * q + 4 * lane_h < g.N) dg_acc[i] += dot;
+            if (m_ok && wcol0 + j * 16 + 4 * lane_c < g.N) dg_acc[i] += dot;
             // each lane overwrites exactly the pieces it has just read
             *reinterpret_cast<u32x2*>(bufA + o) = u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
             *reinterpret_cast<u32x2*>(bufB + o) = u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
             *reinterpret_cast<u32x2*>(bufC + o) = u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
           }
+        }
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
           const int r = t * RPI + cr;
@@ -523,7 +542,7 @@ struct Gemm {
       auto staged = [&](auto tag) {
         using ET = decltype(tag);
         constexpr int ES = sizeof(ET);
-        constexpr int ROWB = TNH * 32 * ES, PIECE = 4 * ES;
+        constexpr int ROWB = TNH * 16 * ES;
         constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
         static_assert(ROWB == 64 || ROWB == 128 || ROWB == 256 || ROWB == 512, "band row");
         static_assert(NP * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
@@ -532,25 +551,24 @@ struct Gemm {
         const int cn = wcol0 + cc * (16 / ES);
         const bool want_h = MODE != UP || g.C0 != nullptr;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int mb = row0 + wm * (TM * 32) + i * 32;
+        for (int ib = 0; ib < NB; ++ib) {
+          const int mb = row0 + wm * (TM * 16) + ib * 32;
 #pragma unroll
-          for (int j = 0; j < TNH; ++j)
+          for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              // 4 columns starting at j*32 + 8q + 4*lane_h of this wavefront's row segment
-              const uint32_t o = ES == 2 ? stage_off<ROWB, PIECE>(lane_m, 4 * j + q) + 8 * lane_h
-                                         : stage_off<ROWB, PIECE>(lane_m, 8 * j + 2 * q + lane_h);
+            for (int j = 0; j < TNH; ++j) {
+              const int i = 2 * ib + i2;
+              const uint32_t o = piece(std::integral_constant<int, ROWB>{}, std::integral_constant<int, ES>{}, i2, j);
               float v[NP][4];
 #pragma unroll
               for (int x = 0; x < 4; ++x) {
                 if constexpr (MODE == UP) {
-                  v[0][x] = acc[i][j][4 * q + x];
-                  v[1][x] = acc[i][j + TNH][4 * q + x];
+                  v[0][x] = acc[i][j][x];
+                  v[1][x] = acc[i][j + TNH][x];
                   v[2][x] = silu_f(v[0][x]) * v[1][x];
                 } else {
 #pragma unroll
-                  for (int pp = 0; pp < NP; ++pp) v[pp][x] = acc[i][j + pp * TNH][4 * q + x];
+                  for (int pp = 0; pp < NP; ++pp) v[pp][x] = acc[i][j + pp * TNH][x];
                 }
               }
 #pragma unroll
@@ -570,7 +588,7 @@ struct Gemm {
 #pragma unroll
             for (int t = 0; t < NI; ++t) {
               const int r = t * RPI + cr;
-              const u32x4 val = *reinterpret_cast<const u32x4*>(wb + pp * (32 * ROWB) + stage_off<ROWB, PIECE>(r, cc));
+              const u32x4 val = *reinterpret_cast<const u32x4*>(wb + pp * (32 * ROWB) + stage_off<ROWB, 4 * ES>(r, cc));
               if (mb + r < row_end && cn < g.N) *reinterpret_cast<u32x4*>(C + (size_t)(mb + r) * g.ldc + cn) = val;
             }
           }
@@ -580,14 +598,15 @@ struct Gemm {
       else staged(bf16_t{});
     }
     if (MODE == BWD_ACT) {
-      // dg partial of this column tile: lanes l and l^32 hold the same row; then the WN
+      // dg partial of this column tile: lanes l, l^16, l^32, l^48 hold the same row; then the WN
       // wavefronts of a row band are summed in fixed order through LDS.
       __syncthreads();  // all waves are done with the operand tiles
       float* red = reinterpret_cast<float*>(smem);   // [WN][BM]
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const float s = dg_acc[i] + __shfl_xor(dg_acc[i], 32, kWave);
-        if (lane_h == 0) red[wn * BM + wm * (TM * 32) + i * 32 + lane_m] = s;
+        float s = dg_acc[i] + __shfl_xor(dg_acc[i], 16, kWave);
+        s += __shfl_xor(s, 32, kWave);
+        if (lane_c == 0) red[wn * BM + wm * (TM * 16) + i * 16 + lane_m] = s;
       }
       __syncthreads();
       for (int r = threadIdx.x; r < BM; r += NT) {
