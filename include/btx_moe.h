@@ -101,8 +101,8 @@ enum {
 int btx_profile_stages(void** events, int n_pairs);
 
 /* Measurement aid, not part of the method: the rate the matrix cores sustain when fed from
- * registers only.  n_blocks workgroups of 8 wavefronts each run `iters` rounds of 64
- * v_mfma_f32_32x32x16_bf16 whose operands (16 fragments per lane, all pairs) are read once
+ * registers only.  n_blocks workgroups of 8 wavefronts each run `iters` rounds of 128
+ * v_mfma_f32_16x16x32_bf16 (the instruction of the expert GEMMs) whose operands (16 fragments per lane, all pairs) are read once
  * from `data` (DEVICE, 16-byte aligned, data_bytes >= 16, any bf16 values: use the kind of
  * data the layer sees, the chip's clock under load depends on it).  out: DEVICE,
  * btx_probe_mfma_out_bytes(n_blocks) bytes, overwritten with meaningless sums.  *flops (HOST,
