@@ -49,7 +49,8 @@ BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   w.dys = ff_gather_fused(dtype, T, d, f) ? nullptr : c.take(R * d * es);
   w.dh1 = c.take(R * f * es);
   w.dh3 = c.take(R * f * es);
-  w.ga = c.take(R * f * es);
+  // transposed path: dW2 reads ga as [f][padded rows]
+  w.ga = c.take(tr ? (size_t)f * ff_dw_pitch((int)R, E) * es : R * f * es);
   w.dxs = c.take(R * d * es);
   w.dg_part = static_cast<float*>(c.take(R * (size_t)bwd_act_partials(dtype, f) * sizeof(float)));
   w.scratch = c.take(ff_scratch_bytes(dtype, (int)R, f));
@@ -256,7 +257,7 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   if (!fused) BTX_STAGE(BTX_STAGE_GATHER_DY, launch_gather_rows(dY, w.dys, perm, R, k, d, dtype, s));
   const RowSource dys = fused ? RowSource{dY, perm, k} : RowSource{w.dys, nullptr, 1};
   BTX_STAGE(BTX_STAGE_BWD_ACT, launch_bwd_act(dtype, dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1,
-                                              w.dh3, w.ga, w.dg_part, w.scratch, s));
+                                              w.dh3, w.ga, n_dw == 3, w.dg_part, w.scratch, s));
   BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s));
   if (n_dw == 3) {
     const bool tr = ff_dw_transposed(dtype, d, f);

@@ -188,17 +188,20 @@ int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void*
 // y = act W2
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
                 hipStream_t s);
-// D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a
+// D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a.
+// dh1, dh3: [R,f].  When ff_dw_transposed() holds, `ga` receives g*a transposed and padded
+// ([f][ff_dw_pitch()]), or nothing at all when want_dw is false; otherwise ga is [R,f].
 int bwd_act_partials(int dtype, int f);
 int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
-                   float* dg_part, void* scratch, hipStream_t s);
+                   bool want_dw, float* dg_part, void* scratch, hipStream_t s);
 // dxs = dh1 W1^T + dh3 W3^T
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
                   const FfShapes& sh, void* dxs, hipStream_t s);
 // dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows.  When
-// ff_dw_transposed() holds, xs and dys are passed in the transposed, padded form that
-// launch_gather_rows_t writes with pitch ff_dw_pitch(); otherwise as grouped rows.
+// ff_dw_transposed() holds, xs, dys and ga are passed in the transposed, padded form with
+// pitch ff_dw_pitch() (xs and dys as launch_gather_rows_t writes them, ga as launch_bwd_act
+// does); otherwise as grouped rows.
 bool ff_dw_transposed(int dtype, int d, int f);
 int ff_dw_pitch(int R, int E);
 int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* offsets,

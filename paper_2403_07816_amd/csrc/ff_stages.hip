@@ -35,9 +35,9 @@ int launch_down(int dtype, const void* act, const void* W2, const int32_t* offse
 }
 int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
-                   float* dg_part, void* scratch, hipStream_t s) {
+                   bool want_dw, float* dg_part, void* scratch, hipStream_t s) {
   if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) {
-    return mfma_bwd_act(dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, s);
+    return mfma_bwd_act(dys, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, want_dw ? ga : nullptr, dg_part, s);
   }
   if (dys.perm) return BTX_ERR_UNSUPPORTED;
   return generic_bwd_act(dtype, dys.base, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, scratch, s);

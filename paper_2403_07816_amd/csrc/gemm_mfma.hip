@@ -15,9 +15,10 @@
 //     between a memory phase and a compute phase (see the main loop);
 //   * an operand whose K index is contiguous in memory is stored [row][BK] with a 16-byte
 //     chunk XOR swizzle and read with ds_read_b128; an operand whose K index is strided
-//     (the weights in UP and DOWN, dh1/dh3/ga in the dW products) is stored as it lies in
-//     memory, [BK][cols], and read with the transposing ds_read_b64_tr_b16; x and dY reach the
-//     dW products already transposed and zero-padded per expert.  The swizzles are applied by choosing which
+//     (the weights in UP and DOWN, dh1/dh3 in DW13) is stored as it lies in memory, [BK][cols],
+//     and read with the transposing ds_read_b64_tr_b16; x, dY and ga reach the dW products
+//     transposed and zero-padded per expert (x and dY from a gather kernel, ga written that way
+//     by BWD_ACT's epilogue).  The swizzles are applied by choosing which
 //     global chunk each lane fetches, since a direct copy fixes the LDS position per lane;
 //   * v_mfma_f32_16x16x32_bf16 (on this chip it sustains a seventh more than the 32x32x16 form
 //     under the same power limit) with the roles of the operands swapped (the N-side fragment
@@ -47,6 +48,7 @@ struct MArgs {
   const bf16_t* B0; const bf16_t* B1;   // B1: second panel (UP, DW13) or second K pass (BWD_DX)
   void* C0; void* C1; void* C2;         // UP: h1,h3,act; BWD_ACT: dh1,dh3,ga; DW13: dW1,dW3; else C0
   const bf16_t* H1; const bf16_t* H3;   // BWD_ACT inputs
+  bf16_t* T2; int ldt;                  // BWD_ACT: ga transposed [N][ldt], experts' rows padded to 64 (NULL: not wanted)
   const float* gates; const int32_t* perm; float* dg_part; int n_part;
   const int32_t* a_perm; int a_k;       // UP / BWD_ACT: A row r is row a_perm[r] / a_k of A0 (NULL: row r)
   const int32_t* offsets; int E;
@@ -104,11 +106,11 @@ __device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
 
 template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 struct Gemm {
-  // K index contiguous in memory?  In the dW products K is the grouped-row index: the operand
-  // with d columns (x for dW1/dW3, dY for dW2) arrives transposed, [d][padded rows], every
-  // expert's rows starting at a multiple of 64 and zero-filled up to the next one.
-  static constexpr bool A_KC = (MODE != DW2);
-  static constexpr bool B_KC = (MODE == BWD_ACT || MODE == BWD_DX || MODE == DW2);
+  // K index contiguous in memory?  A always is.  In the dW products K is the grouped-row index:
+  // x (dW1/dW3) and ga, dY (dW2) arrive transposed, [columns][padded rows], every expert's rows
+  // starting at a multiple of 64 and zero-filled up to the next one; dh1/dh3 stay row-major.
+  static constexpr bool A_KC = true;
+  static constexpr bool B_KC = (MODE != UP && MODE != DOWN && MODE != DW13);
   static constexpr bool DUAL = (MODE == UP || MODE == DW13);
   static constexpr bool GROUP_K = (MODE == DW13 || MODE == DW2);
   static constexpr int NW = WM * WN, NT = NW * kWave;
@@ -235,6 +237,8 @@ struct Gemm {
       if (!find_row_tile(g.offsets, g.E, BM, tile_m, e, row0, row_end)) return;
       k_begin = 0;
       k_end = g.K;
+      if (MODE == BWD_ACT && g.T2)                      // where expert e starts in the transposed outputs
+        for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
     }
     const int col0 = tile_n * BNH;
 
@@ -246,26 +250,18 @@ struct Gemm {
     // KC operand:      base = P + row0*ld + k0,  offset = (clamp(row) - row0)*ld + k_in_tile
     // strided operand: base = P + k0*ld,         offset = k_in_tile*ld + clamp(col)
     uint32_t a_off[A_LOADS], b_off[B_LOADS];
-    int a_k[A_LOADS], b_k[B_LOADS], a_c[A_LOADS], b_c[B_LOADS];   // strided layouts: k row / column
+    int b_k[B_LOADS], b_c[B_LOADS];                               // strided layout: k row / column
     bool b_second[B_LOADS];
     bool a_hi[A_LOADS], b_hi[B_LOADS];                            // KC layouts: chunk lies in the upper 32 k of the tile
 #pragma unroll
     for (int q = 0; q < A_LOADS; ++q) {
       int major, minor;
       copy_coords<A_KC, BM>(wave * A_LOADS + q, lane, major, minor);
-      if (A_KC) {
-        const int gr = min(row0 + major, row_end - 1);
-        // gathered rows: the offset is taken from the first row of A0 (it fits 32 bits, checked on the host)
-        a_off[q] = g.a_perm ? (uint32_t)(g.a_perm[gr] / g.a_k) * (uint32_t)(g.lda * 2) + (uint32_t)(minor * 2)
-                            : (uint32_t)((gr - row0) * g.lda + minor) * 2u;
-        a_k[q] = a_c[q] = 0;
-        a_hi[q] = minor >= 32;
-      } else {
-        a_hi[q] = false;
-        a_k[q] = major;
-        a_c[q] = min(row0 + minor, row_end - 8);
-        a_off[q] = (uint32_t)(major * g.lda + a_c[q]) * 2u;
-      }
+      const int gr = min(row0 + major, row_end - 1);
+      // gathered rows: the offset is taken from the first row of A0 (it fits 32 bits, checked on the host)
+      a_off[q] = g.a_perm ? (uint32_t)(g.a_perm[gr] / g.a_k) * (uint32_t)(g.lda * 2) + (uint32_t)(minor * 2)
+                          : (uint32_t)((gr - row0) * g.lda + minor) * 2u;
+      a_hi[q] = minor >= 32;
     }
 #pragma unroll
     for (int q = 0; q < B_LOADS; ++q) {
@@ -276,10 +272,10 @@ struct Gemm {
       const int seg = wave * B_LOADS + q;
       copy_coords<B_KC, BNH>(seg % SEGS_PER_PANEL, lane, major, minor);
       if (B_KC) {
-        // tile rows are output columns; BWD_DX / BWD_ACT have a single panel
+        // tile rows are output columns (DUAL: BNH of the first panel, then BNH of the second)
         b_off[q] = (uint32_t)((min(col0 + major, g.N - 1) - col0) * g.ldb + minor) * 2u;
         b_k[q] = b_c[q] = 0;
-        b_second[q] = false;
+        b_second[q] = DUAL && seg >= SEGS_PER_PANEL;
         b_hi[q] = minor >= 32;
       } else {
         b_hi[q] = false;
@@ -312,13 +308,11 @@ struct Gemm {
       const int k0 = tile_k0(kt, A_KC, pass2);
       const uint32_t stage = smem_base + (kt % NSA) * A_BYTES;
       const bf16_t* Ab = pass2 ? g.A1 : g.A0;
-      Ab += A_KC ? (g.a_perm ? (size_t)0 : (size_t)row0 * g.lda) + k0 : (size_t)k0 * g.lda;
+      Ab += (g.a_perm ? (size_t)0 : (size_t)row0 * g.lda) + k0;
 #pragma unroll
       for (int q = 0; q < A_LOADS; ++q) {
         uint32_t off = a_off[q];
-        // grouped-K: a k row past the last grouped row is re-pointed at row R-1 (it meets zeros)
-        if (!A_KC) off = (uint32_t)((min(k0 + a_k[q], g.R - 1) - k0) * g.lda + a_c[q]) * 2u;
-        if (A_KC && a_hi[q] && is_tail(kt)) off -= 64u;
+        if (a_hi[q] && is_tail(kt)) off -= 64u;
         copy16_to_lds(Ab, off, stage + (wave * A_LOADS + q) * 1024);
       }
     };
@@ -331,6 +325,7 @@ struct Gemm {
 #pragma unroll
       for (int q = 0; q < B_LOADS; ++q) {
         uint32_t off = b_off[q];
+        // grouped-K, strided operand: a k row past the last grouped row is re-pointed at row R-1 (it meets zeros)
         if (GROUP_K && !B_KC) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
         if (is_tail(kt)) {
           if (B_KC) { if (b_hi[q]) off -= 64u; }
@@ -355,12 +350,13 @@ struct Gemm {
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int r = wm * (TM * 16) + i * 16;
-        af[i] = A_KC ? read_kc(At, r, ks, lane) : read_tr<BM>(At, r, ks, lane);
+        af[i] = read_kc(At, r, ks, lane);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int c = wn * (TNH * 16) + (j % TNH) * 16;
-        bfr[j] = B_KC ? read_kc(Bt, c, ks, lane) : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
+        bfr[j] = B_KC ? read_kc(Bt, (j / TNH) * BNH + c, ks, lane)
+                      : read_tr<BNH>(Bt + (j / TNH) * (BK * BNH * 2), c, ks, lane);
       }
     };
     auto mfma_step = [&](bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
@@ -493,8 +489,8 @@ struct Gemm {
 #pragma unroll
         for (int i2 = 0; i2 < 2; ++i2) {
           const int i = 2 * ib + i2;
-          const float gate = gate2[i2];
           const bool m_ok = mb + i2 * 16 + lane_m < row_end;
+          const float gate = m_ok ? gate2[i2] : 0.f;    // rows past the group's end come out as zeros
 #pragma unroll
           for (int j = 0; j < TNH; ++j) {
             const uint32_t o = piece(std::integral_constant<int, ROWB>{}, std::integral_constant<int, 2>{}, i2, j);
@@ -532,8 +528,49 @@ struct Gemm {
             const size_t idx = (size_t)(mb + r) * g.ldc + cn;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = v1;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = v3;
-            *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = va;
+            if (g.C2) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = va;
           }
+        }
+        if (g.T2) {
+          // The same band once more, transposed, for the dW products: [column][padded grouped row].
+          // A pair of transposing reads turns 16 columns x 8 rows per 16-lane group around: lane
+          // 4a+b of a group receives element b of what lanes a, a+4, a+8, a+12 fetched, so lane r
+          // fetches band row 8*group + r/4 (then +4) at columns 4*(r%4).. and ends up with rows
+          // 8*group .. +7 of column r: 16 contiguous bytes of the transposed matrix.  Those go
+          // back into the same buffer as [column][32 rows] (64 bytes per column, chunks swizzled
+          // by column) and are read so that four consecutive lanes hold one column's 64 bytes:
+          // scattered 16-byte stores cost the address unit four times as much.  Rows past the
+          // group's end are zeros (see the gate above) and are written up to the 64-row padding.
+          typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+          const int o_e = g.offsets[e];
+          const int pad_e = (row_end - o_e + 63) & ~63;
+          const int fr = 8 * lane_c + (lane_m >> 2), fa4 = lane_m & 3;
+          const int qc = lane >> 2, qg = lane & 3;        // read-back view: column within 16, 8-row chunk
+          const int m8 = mb + 8 * qg - o_e;              // grouped row of that chunk, relative to the expert
+          auto turn = [&](char* buf, bf16_t* T) {
+            bf16x8 v[TNH];
+#pragma unroll
+            for (int pr = 0; pr < TNH; ++pr) {
+              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+              const uint32_t o_hi = stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+              const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_lo));
+              const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_hi));
+              v[pr] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+#pragma unroll
+            for (int pr = 0; pr < TNH; ++pr) {
+              const int tc = 16 * pr + lane_m;
+              *reinterpret_cast<bf16x8*>(buf + tc * 64 + ((lane_c ^ ((tc >> 2) & 3)) << 4)) = v[pr];
+            }
+#pragma unroll
+            for (int pr = 0; pr < TNH; ++pr) {
+              const int tc = 16 * pr + qc;
+              const bf16x8 w = *reinterpret_cast<const bf16x8*>(buf + tc * 64 + ((qg ^ ((tc >> 2) & 3)) << 4));
+              const int col = wcol0 + tc;
+              if (col < g.N && m8 < pad_e) *reinterpret_cast<bf16x8*>(T + (size_t)col * g.ldt + kp_begin + m8) = w;
+            }
+          };
+          turn(bufC, g.T2);
         }
       }
     } else {
@@ -687,12 +724,13 @@ int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShape
 }
 
 int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
-                 const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* ga,
+                 const int32_t* perm, const int32_t* off, const FfShapes& sh, void* dh1, void* dh3, void* gaT,
                  float* dg_part, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
   g.A0 = (const bf16_t*)dys.base; g.a_perm = dys.perm; g.a_k = dys.k;
-  g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = ga;
+  g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = nullptr;
+  g.T2 = (bf16_t*)gaT; g.ldt = mfma_dw_pitch(sh.R, sh.E);
   g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3; g.gates = gates; g.perm = perm; g.dg_part = dg_part;
   g.n_part = mfma_bwd_act_partials(sh.f);
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.d; g.ldc = sh.f;
@@ -724,14 +762,14 @@ int mfma_bwd_dw13(int dW_dtype, const void* xsT, const void* dh1, const void* dh
   return launch<256, 256, 64, 2, 4, 3, 2, DW13>(g, s);
 }
 
-int mfma_bwd_dw2(int dW_dtype, const void* ga, const void* dysT, const int32_t* off, const FfShapes& sh, void* dW2,
+int mfma_bwd_dw2(int dW_dtype, const void* gaT, const void* dysT, const int32_t* off, const FfShapes& sh, void* dW2,
                  hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs h{};
-  h.A0 = (const bf16_t*)ga; h.B0 = (const bf16_t*)dysT; h.C0 = dW2;
-  h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = sh.f; h.ldb = mfma_dw_pitch(sh.R, sh.E); h.ldc = sh.d;
+  h.A0 = (const bf16_t*)gaT; h.B0 = (const bf16_t*)dysT; h.C0 = dW2;
+  h.offsets = off; h.E = sh.E; h.M = sh.f; h.N = sh.d; h.lda = h.ldb = mfma_dw_pitch(sh.R, sh.E); h.ldc = sh.d;
   h.strideC_e = sh.s2; h.R = sh.R; h.c_is_f32 = dW_dtype == BTX_F32;
-  return launch<256, 256, 64, 4, 2, 3, 2, DW2>(h, s);
+  return launch<256, 256, 64, 2, 4, 3, 2, DW2>(h, s);
 }
 
 }  // namespace btx
