@@ -46,7 +46,7 @@ enum Mode { UP = 0, DOWN = 1, BWD_ACT = 2, BWD_DX = 3, DW13 = 4, DW2 = 5 };
 struct MArgs {
   const bf16_t* A0; const bf16_t* A1;   // A1: second K pass (BWD_DX)
   const bf16_t* B0; const bf16_t* B1;   // B1: second panel (UP, DW13) or second K pass (BWD_DX)
-  void* C0; void* C1; void* C2;         // UP: h1,h3,act; BWD_ACT: dh1,dh3,ga; DW13: dW1,dW3; else C0
+  void* C0; void* C1; void* C2;         // UP: h1,h3,act; BWD_ACT: dh1,dh3 (ga goes to T2); DW13: dW1,dW3; else C0
   const bf16_t* H1; const bf16_t* H3;   // BWD_ACT inputs
   bf16_t* T2; int ldt;                  // BWD_ACT: ga transposed [N][ldt], experts' rows padded to 64 (NULL: not wanted)
   const float* gates; const int32_t* perm; float* dg_part; int n_part;
@@ -514,7 +514,7 @@ struct Gemm {
             // each lane overwrites exactly the pieces it has just read
             *reinterpret_cast<u32x2*>(bufA + o) = u32x2{pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3])};
             *reinterpret_cast<u32x2*>(bufB + o) = u32x2{pack_bf16x2(o3[0], o3[1]), pack_bf16x2(o3[2], o3[3])};
-            *reinterpret_cast<u32x2*>(bufC + o) = u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
+            if (g.T2) *reinterpret_cast<u32x2*>(bufC + o) = u32x2{pack_bf16x2(oa[0], oa[1]), pack_bf16x2(oa[2], oa[3])};
           }
         }
 #pragma unroll
@@ -523,12 +523,10 @@ struct Gemm {
           const uint32_t o = stage_off<ROWB, 8>(r, cc);
           const u32x4 v1 = *reinterpret_cast<const u32x4*>(bufA + o);
           const u32x4 v3 = *reinterpret_cast<const u32x4*>(bufB + o);
-          const u32x4 va = *reinterpret_cast<const u32x4*>(bufC + o);
           if (mb + r < row_end && cn < g.N) {
             const size_t idx = (size_t)(mb + r) * g.ldc + cn;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = v1;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C1) + idx) = v3;
-            if (g.C2) *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C2) + idx) = va;
           }
         }
         if (g.T2) {
@@ -729,7 +727,7 @@ int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const voi
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
   g.A0 = (const bf16_t*)dys.base; g.a_perm = dys.perm; g.a_k = dys.k;
-  g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3; g.C2 = nullptr;
+  g.B0 = (const bf16_t*)W2; g.C0 = dh1; g.C1 = dh3;
   g.T2 = (bf16_t*)gaT; g.ldt = mfma_dw_pitch(sh.R, sh.E);
   g.H1 = (const bf16_t*)h1; g.H3 = (const bf16_t*)h3; g.gates = gates; g.perm = perm; g.dg_part = dg_part;
   g.n_part = mfma_bwd_act_partials(sh.f);
