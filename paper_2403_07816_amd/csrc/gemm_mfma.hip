@@ -629,8 +629,12 @@ struct Gemm {
           }
         }
       };
-      if (GROUP_K && g.c_is_f32) staged(float{});
-      else staged(bf16_t{});
+      if constexpr (GROUP_K) {                       // only the weight gradients can be asked for in fp32
+        if (g.c_is_f32) staged(float{});
+        else staged(bf16_t{});
+      } else {
+        staged(bf16_t{});
+      }
     }
     if (MODE == BWD_ACT) {
       // dg partial of this column tile: lanes l, l^16, l^32, l^48 hold the same row; then the WN
