@@ -222,7 +222,7 @@ def main():
     grads = B.Grads(torch.empty_like(L["x"]), torch.empty((d, E), dtype=torch.float32, device=dev),
                     torch.empty(E, dtype=torch.float32, device=dev), torch.empty_like(L["W1"]),
                     torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
-    ws_bytes = max(lib.btx_moe_route_workspace_bytes(T, E, k),
+    ws_bytes = max(lib.btx_moe_route_workspace_bytes(T, d, E, k),
                    lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
                    lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)

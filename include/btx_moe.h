@@ -145,9 +145,9 @@ int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks
  *   prob_sum   [E]     fp32 sum_t softmax_{t,e}
  *   lb_loss    [1]     fp32 lb_alpha * E * sum_e u_e * prob_sum_e / T
  * Requirements: 1 <= k <= E <= 64; d % 8 == 0; SWITCH/SAMPLE/GUMBEL need k == 1;
- * T*k < 2^31.  workspace >= btx_moe_route_workspace_bytes(T,E,k).
+ * T*k < 2^31.  workspace >= btx_moe_route_workspace_bytes(T,d,E,k).
  */
-size_t btx_moe_route_workspace_bytes(int T, int E, int k);
+size_t btx_moe_route_workspace_bytes(int T, int d, int E, int k);
 int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U,
                   int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau,
                   float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,

@@ -31,7 +31,7 @@ _SIGNATURES = {
     "btx_profile_stages": (_i, [ctypes.POINTER(_vp), _i]),
     "btx_probe_mfma_out_bytes": (_sz, [_i]),
     "btx_probe_mfma": (_i, [_vp, _sz, _vp, _i, _i, ctypes.POINTER(ctypes.c_double), _vp]),
-    "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i]),
+    "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_norm_route": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 +
                            [_vp, _sz, _vp]),
@@ -132,7 +132,7 @@ def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[to
     E = W_router.shape[1]
     assert W_router.shape[0] == d and W_router.dtype == torch.float32
     r = out if out is not None else alloc_routing(T, E, k, x.device)
-    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), x.device, workspace)
+    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, d, E, k), x.device, workspace)
     st = lib.btx_moe_route(_ptr(x), _dtype_code(x), _ptr(W_router), _ptr(b_router), _ptr(U), T, d, E, k, route_mode,
                            lb_mode, lb_alpha, tau, capacity_factor, _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts),
                            _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum),
@@ -156,7 +156,7 @@ def btx_moe_norm_route(h: torch.Tensor, gain: torch.Tensor, eps: float, W_router
     r = out if out is not None else alloc_routing(T, E, k, h.device)
     xn = xn if xn is not None else torch.empty_like(h)
     rstd = rstd if rstd is not None else torch.empty(T, dtype=torch.float32, device=h.device)
-    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, E, k), h.device, workspace)
+    ws = _workspace(lib.btx_moe_route_workspace_bytes(T, d, E, k), h.device, workspace)
     st = lib.btx_moe_norm_route(_ptr(h), _dtype_code(h), _ptr(gain), eps, _ptr(xn), _ptr(rstd), _ptr(W_router),
                                 _ptr(b_router), _ptr(U), T, d, E, k, route_mode, lb_mode, lb_alpha, tau, capacity_factor,
                                 _ptr(r.topk_idx), _ptr(r.gates), _ptr(r.probs), _ptr(r.counts), _ptr(r.offsets),

@@ -109,9 +109,9 @@ int btx_profile_stages(void** events, int n_pairs) {
   return BTX_OK;
 }
 
-size_t btx_moe_route_workspace_bytes(int T, int E, int k) {
-  if (T <= 0 || E < 1 || E > kMaxExperts || k < 1 || k > E) return 0;
-  return route_workspace_bytes(T, E, k);
+size_t btx_moe_route_workspace_bytes(int T, int d, int E, int k) {
+  if (T <= 0 || d <= 0 || E < 1 || E > kMaxExperts || k < 1 || k > E) return 0;
+  return route_workspace_bytes(T, d, E, k);
 }
 
 namespace {
@@ -135,7 +135,7 @@ int route_impl(const void* x, int x_dtype, const float* gain, float eps, void* x
   if (!x || !W_router || !topk_idx || !gates || !probs || !counts || !offsets || !perm || !inv_pos || !gate_sum ||
       !prob_sum || !lb_loss || !workspace)
     return BTX_ERR_INVALID_ARG;
-  if (workspace_bytes < route_workspace_bytes(T, E, k)) return BTX_ERR_WORKSPACE;
+  if (workspace_bytes < route_workspace_bytes(T, d, E, k)) return BTX_ERR_WORKSPACE;
   // capacity in double, as the specification of the limit is ceil(cf * T*k / E) over the reals
   const double cap_d = capacity_factor > 0.f ? std::ceil((double)capacity_factor * T * k / E) : 0.0;
   const int cap = cap_d > (double)T * k ? T * k : (int)cap_d;

@@ -49,6 +49,31 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// N consecutive elements of a row (N = 8; the address is N-element aligned) as floats
+template <typename T, int N> struct RowVec;
+template <> struct RowVec<bf16_t, 8> {
+  static __device__ __forceinline__ void ld(const bf16_t* p, float* v) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, const float* v) {
+    *reinterpret_cast<u32x4*>(p) =
+        u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+  }
+};
+template <> struct RowVec<float, 8> {
+  static __device__ __forceinline__ void ld(const float* p, float* v) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+  static __device__ __forceinline__ void st(float* p, const float* v) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+  }
+};
+
 // sigmoid via the hardware exp2 and reciprocal (about 1 ulp each): far inside the fp32 bar
 __device__ __forceinline__ float sigmoid_f(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 __device__ __forceinline__ float silu_f(float z) { return z * sigmoid_f(z); }
@@ -157,12 +182,14 @@ struct RouteArgs {
   // the raw row, xn [T,d] (x's dtype) receives gain * x * rstd and rstd [T] the row factors
   const float* gain; float eps; void* xn; float* rstd;
 };
-size_t route_workspace_bytes(int T, int E, int k);
+size_t route_workspace_bytes(int T, int d, int E, int k);
 // backward of the normalisation: dH = d(xn)/d(h)^T dXn (+ dres), dgain[c] = sum_t dXn[t,c] h[t,c] rstd[t]
 size_t rmsnorm_bwd_workspace_bytes(int T, int d);
 int launch_rmsnorm_bwd(const void* dXn, const void* h, const float* gain, const float* rstd, const void* dres,
                        int dtype, int T, int d, void* dH, float* dgain, void* workspace, hipStream_t s);
 int launch_route(const RouteArgs& a, hipStream_t s);
+// WrT[e][c] = Wr[c][e]: the router kernels read W_router expert-major
+int launch_transpose_wr(const float* Wr, int d, int E, float* WrT, hipStream_t s);
 
 // rows: dst[r] = src[perm[r] / k]  (k = 1 with perm = NULL copies nothing; perm required)
 int launch_gather_rows(const void* src, void* dst, const int32_t* perm, int R, int k, int d, int dtype, hipStream_t s);

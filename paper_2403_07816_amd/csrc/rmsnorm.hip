@@ -15,30 +15,6 @@ namespace {
 constexpr int kNormTok = 16;     // tokens per workgroup
 constexpr int kNormThreads = 256;
 
-template <typename XT> struct Row8;
-template <> struct Row8<bf16_t> {
-  static __device__ __forceinline__ void ld(const bf16_t* p, float* v) {
-    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
-  }
-  static __device__ __forceinline__ void st(bf16_t* p, const float* v) {
-    *reinterpret_cast<u32x4*>(p) =
-        u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
-  }
-};
-template <> struct Row8<float> {
-  static __device__ __forceinline__ void ld(const float* p, float* v) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
-  }
-  static __device__ __forceinline__ void st(float* p, const float* v) {
-    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
-    *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
-  }
-};
-
 // MAXC: 8-column chunks a thread owns (d <= MAXC * 2048); its column sums stay in registers
 template <typename XT, int MAXC>
 // dH may be the same buffer as dXn or dres (every thread writes only the chunks it has read, and a
@@ -60,13 +36,13 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_bwd_kernel(const XT* dXn
       const int c0 = (m * kNormThreads + threadIdx.x) * 8;
       if (c0 < d) {
         float gv[8];
-        Row8<float>::ld(gain + c0, gv);
+        RowVec<float, 8>::ld(gain + c0, gv);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const size_t row = (size_t)min(t0 + tq + q, T - 1) * d + c0;   // clamped rows are computed and dropped
           float a[8], b[8];
-          Row8<XT>::ld(dXn + row, a);
-          Row8<XT>::ld(h + row, b);
+          RowVec<XT, 8>::ld(dXn + row, a);
+          RowVec<XT, 8>::ld(h + row, b);
 #pragma unroll
           for (int i = 0; i < 8; ++i) sq[q] = fmaf(gv[i] * a[i], b[i], sq[q]);
         }
@@ -92,7 +68,7 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_bwd_kernel(const XT* dXn
       const int c0 = (m * kNormThreads + threadIdx.x) * 8;
       if (c0 < d) {
         float gv[8];
-        Row8<float>::ld(gain + c0, gv);
+        RowVec<float, 8>::ld(gain + c0, gv);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int t = t0 + tq + q;
@@ -100,8 +76,8 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_bwd_kernel(const XT* dXn
             const size_t row = (size_t)t * d + c0;
             const float r = rstd[t], coef = s_coef[q];
             float a[8], b[8], o[8];
-            Row8<XT>::ld(dXn + row, a);
-            Row8<XT>::ld(h + row, b);
+            RowVec<XT, 8>::ld(dXn + row, a);
+            RowVec<XT, 8>::ld(h + row, b);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
               o[i] = r * gv[i] * a[i] - b[i] * coef;
@@ -109,11 +85,11 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_bwd_kernel(const XT* dXn
             }
             if (dres) {
               float e[8];
-              Row8<XT>::ld(dres + row, e);
+              RowVec<XT, 8>::ld(dres + row, e);
 #pragma unroll
               for (int i = 0; i < 8; ++i) o[i] += e[i];
             }
-            Row8<XT>::st(dH + row, o);
+            RowVec<XT, 8>::st(dH + row, o);
           }
         }
       }
@@ -123,7 +99,7 @@ __global__ __launch_bounds__(kNormThreads) void rmsnorm_bwd_kernel(const XT* dXn
 #pragma unroll
   for (int m = 0; m < MAXC; ++m) {
     const int c0 = (m * kNormThreads + threadIdx.x) * 8;
-    if (c0 < d) Row8<float>::st(part + (size_t)blockIdx.x * d + c0, gacc[m]);
+    if (c0 < d) RowVec<float, 8>::st(part + (size_t)blockIdx.x * d + c0, gacc[m]);
   }
 }
 

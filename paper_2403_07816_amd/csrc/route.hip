@@ -2,21 +2,26 @@
 // the stable grouping of (token, slot) pairs by expert (Sec. 3.2 router and Top-k;
 // Sec. 3.3 load balancing, Switch and sample-top-1 routing).
 //
-// Three launches, no atomics, no host round trip:
+// Four launches, no atomics, no host round trip:
 //   (optional) the RMS normalisation in front of the sublayer (the seed model's blocks
 //   normalise before their feed-forward, Sec. 4.1) is folded into route_tokens: the raw rows
 //   are read once more for their mean square (fp64), the normalised, rounded rows are written
 //   out for the expert GEMMs and are what the logits are computed from.
+//   0. transpose_wr   W_router [d,E] -> [E,d] in the workspace: a lane then reads its 8 columns of
+//                     an expert as 32 contiguous bytes and a wavefront's load covers 2 KB in one
+//                     piece, where the [d,E] form costs one cache line per lane and load.
 //   1. route_tokens   one wavefront handles kTokPerWave tokens at a time: fp32 dot
 //                     products of the token row with W_router (lanes split the row,
 //                     butterfly reduction), then softmax / selection / gates with one
 //                     lane per expert.  Each workgroup owns kTokPerBlock consecutive
 //                     tokens and writes its per-expert counts and gate/prob sums.
-//   2. route_scan     one workgroup: per-expert exclusive scan of the block counts
-//                     (fixed order), expert offsets, finished statistics and lb_loss.
-//   3. route_scatter  one wavefront per block re-reads its indices and writes perm and
+//   2. route_scan     one workgroup per expert: exclusive scan of its block counts (fixed
+//                     order) and its finished statistics.
+//   3. route_scatter  every wavefront rebuilds the expert offsets from the counts (one lane per
+//                     expert); one wavefront per block re-reads its indices and writes perm and
 //                     inv_pos; ranks inside a block come from wavefront ballots, so the
-//                     order inside every expert group is the (token, slot) order.
+//                     order inside every expert group is the (token, slot) order.  The first
+//                     wavefront also writes offsets and lb_loss.
 #include "common.h"
 
 namespace btx {
@@ -26,23 +31,6 @@ constexpr int kTokPerWave = 4;
 constexpr int kWavesPerBlock = 4;
 constexpr int kTokPerBlock = kTokPerWave * kWavesPerBlock;  // 16 consecutive tokens per workgroup
 constexpr int kScanThreads = 1024;
-
-template <typename XT> struct RowLoad;
-template <> struct RowLoad<bf16_t> {
-  static __device__ __forceinline__ void ld8(const bf16_t* p, float* v) {
-    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
-  }
-};
-template <> struct RowLoad<float> {
-  static __device__ __forceinline__ void ld8(const float* p, float* v) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(p);
-    const f32x4 b = *reinterpret_cast<const f32x4*>(p + 4);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
-  }
-};
 
 // normalised value, rounded once to the row's storage type; `back` is that value again as float
 template <typename XT> struct NormRound;
@@ -99,10 +87,10 @@ __device__ __forceinline__ float wave_incl_scan(float v, int lane) {
 }
 
 // EC experts are accumulated per pass over the row; kTokPerWave tokens share each
-// W_router load.
+// load of the (transposed) W_router.
 template <typename XT, int EC, bool NORM>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
-    const XT* __restrict__ x, const float* __restrict__ Wr, const float* __restrict__ br,
+    const XT* __restrict__ x, const float* __restrict__ WrT, const float* __restrict__ br,
     const float* __restrict__ U, int T, int d, int E, int k, int mode, float inv_tau, int32_t* __restrict__ topk_idx,
     float* __restrict__ gates, float* __restrict__ probs, int32_t* __restrict__ blk_counts,
     float* __restrict__ blk_gsum, float* __restrict__ blk_psum, const float* __restrict__ gain, float eps,
@@ -112,7 +100,6 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int t0 = blockIdx.x * kTokPerBlock + wave * kTokPerWave;
-  const bool vec4 = (E % EC) == 0 && (E % 4) == 0;
 
   // ---- row factors of the normalisation -------------------------------------
   // fp64 throughout: the rounded rows then agree with a host fp64 evaluation except where the
@@ -124,7 +111,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
 #pragma unroll
       for (int q = 0; q < kTokPerWave; ++q) {
         float v[8];
-        RowLoad<XT>::ld8(x + (size_t)min(t0 + q, T - 1) * d + c0, v);
+        RowVec<XT, 8>::ld(x + (size_t)min(t0 + q, T - 1) * d + c0, v);
 #pragma unroll
         for (int i = 0; i < 8; ++i) ss[q] += (double)v[i] * (double)v[i];
       }
@@ -148,11 +135,11 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
 #pragma unroll
       for (int q = 0; q < kTokPerWave; ++q) {
         const int t = min(t0 + q, T - 1);  // clamped rows are computed and then dropped
-        RowLoad<XT>::ld8(x + (size_t)t * d + c0, xv[q]);
+        RowVec<XT, 8>::ld(x + (size_t)t * d + c0, xv[q]);
       }
       if (NORM) {
         float gv[8];
-        RowLoad<float>::ld8(gain + c0, gv);
+        RowVec<float, 8>::ld(gain + c0, gv);
 #pragma unroll
         for (int q = 0; q < kTokPerWave; ++q) {
           XT h[8];
@@ -162,23 +149,13 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
         }
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float w[EC];
-        const float* wp = Wr + (size_t)(c0 + i) * E + e0;
-        if (EC % 4 == 0 && vec4) {   // E % 4 == 0: whole 16-byte groups, all inside the row
-#pragma unroll
-          for (int j = 0; j < EC; j += 4) {
-            const f32x4 wv = *reinterpret_cast<const f32x4*>(wp + j);
-            w[j] = wv[0]; w[j + 1] = wv[1]; w[j + 2] = wv[2]; w[j + 3] = wv[3];
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < EC; ++j) w[j] = (e0 + j < E) ? wp[j] : 0.f;
-        }
+      for (int j = 0; j < EC; ++j) {
+        float w[8] = {};
+        if (e0 + j < E) RowVec<float, 8>::ld(WrT + (size_t)(e0 + j) * d + c0, w);
 #pragma unroll
         for (int q = 0; q < kTokPerWave; ++q)
 #pragma unroll
-          for (int j = 0; j < EC; ++j) acc[q][j] = fmaf(xv[q][i], w[j], acc[q][j]);
+          for (int i = 0; i < 8; ++i) acc[q][j] = fmaf(xv[q][i], w[i], acc[q][j]);
       }
     }
 #pragma unroll
@@ -288,80 +265,86 @@ __device__ __forceinline__ int block_excl_scan(int v, int& total, int* s_wave) {
   return base + incl - v;
 }
 
+// one workgroup per expert
 __global__ __launch_bounds__(kScanThreads) void route_scan_kernel(
-    int nblk, int T, int E, int k, int cap, int lb_mode, float lb_alpha, const int32_t* __restrict__ blk_counts,
-    const float* __restrict__ blk_gsum, const float* __restrict__ blk_psum, int32_t* __restrict__ blk_base,
-    int32_t* __restrict__ counts, int32_t* __restrict__ offsets, float* __restrict__ gate_sum,
-    float* __restrict__ prob_sum, float* __restrict__ lb_loss, int32_t* __restrict__ perm) {
-  __shared__ int s_kept_total;
+    int nblk, int E, const int32_t* __restrict__ blk_counts, const float* __restrict__ blk_gsum,
+    const float* __restrict__ blk_psum, int32_t* __restrict__ blk_base, int32_t* __restrict__ counts,
+    float* __restrict__ gate_sum, float* __restrict__ prob_sum) {
   __shared__ int s_wave[kScanThreads / kWave];
-  __shared__ int s_count[kMaxExperts];
   __shared__ float s_red[2][kScanThreads / kWave];
-  __shared__ float s_g[kMaxExperts], s_p[kMaxExperts];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  for (int e = 0; e < E; ++e) {
-    int running = 0;
-    float g = 0.f, p = 0.f;
-    for (int b0 = 0; b0 < nblk; b0 += kScanThreads) {
-      const int b = b0 + threadIdx.x;
-      const int v = b < nblk ? blk_counts[(size_t)b * E + e] : 0;
-      int total;
-      const int ex = block_excl_scan(v, total, s_wave);
-      if (b < nblk) {
-        blk_base[(size_t)b * E + e] = running + ex;
-        g += blk_gsum[(size_t)b * E + e];
-        p += blk_psum[(size_t)b * E + e];
-      }
-      running += total;
+  const int e = blockIdx.x;
+  int running = 0;
+  float g = 0.f, p = 0.f;
+  for (int b0 = 0; b0 < nblk; b0 += kScanThreads) {
+    const int b = b0 + threadIdx.x;
+    const int v = b < nblk ? blk_counts[(size_t)b * E + e] : 0;
+    int total;
+    const int ex = block_excl_scan(v, total, s_wave);
+    if (b < nblk) {
+      blk_base[(size_t)b * E + e] = running + ex;
+      g += blk_gsum[(size_t)b * E + e];
+      p += blk_psum[(size_t)b * E + e];
     }
-    // fixed-order reduction of the per-thread partial sums
-    g = wave_sum(g);
-    p = wave_sum(p);
-    if (lane == 0) { s_red[0][wave] = g; s_red[1][wave] = p; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      float gs = 0.f, ps = 0.f;
-      for (int w = 0; w < kScanThreads / kWave; ++w) { gs += s_red[0][w]; ps += s_red[1][w]; }
-      s_count[e] = running;
-      s_g[e] = gs;
-      s_p[e] = ps;
-    }
-    __syncthreads();
+    running += total;
   }
-  if (threadIdx.x == 0) {
-    int off = 0;
-    float loss = 0.f;
-    for (int e = 0; e < E; ++e) {
-      offsets[e] = off;
-      counts[e] = s_count[e];
-      gate_sum[e] = s_g[e];
-      prob_sum[e] = s_p[e];
-      const float u = lb_mode == BTX_LB_TOKEN_FRAC ? (float)s_count[e] / ((float)T * (float)k) : s_g[e] / (float)T;
-      loss += u * (s_p[e] / (float)T);
-      // capacity: an expert keeps its first `cap` pairs; the statistics above see the routing
-      off += cap > 0 ? min(s_count[e], cap) : s_count[e];
-    }
-    offsets[E] = off;
-    *lb_loss = lb_alpha * (float)E * loss;
-    s_kept_total = off;
-  }
+  // fixed-order reduction of the per-thread partial sums
+  g = wave_sum(g);
+  p = wave_sum(p);
+  if (lane == 0) { s_red[0][wave] = g; s_red[1][wave] = p; }
   __syncthreads();
-  // grouped rows past the kept ones do not exist; whoever indexes through perm there
-  // (kernels that run over all T*k rows) must still find a valid pair
-  for (int r = s_kept_total + threadIdx.x; r < T * k; r += kScanThreads) perm[r] = 0;
+  if (threadIdx.x == 0) {
+    float gs = 0.f, ps = 0.f;
+    for (int w = 0; w < kScanThreads / kWave; ++w) { gs += s_red[0][w]; ps += s_red[1][w]; }
+    counts[e] = running;
+    gate_sum[e] = gs;
+    prob_sum[e] = ps;
+  }
 }
 
+// grid: one wavefront per token block, plus workgroups that only clear perm's tail
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_scatter_kernel(
-    int nblk, int T, int E, int k, int cap, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ blk_base,
-    const int32_t* __restrict__ offsets, int32_t* __restrict__ perm, int32_t* __restrict__ inv_pos) {
+    int nblk, int T, int E, int k, int cap, int lb_mode, float lb_alpha, const int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ blk_base, const int32_t* __restrict__ counts, const float* __restrict__ gate_sum,
+    const float* __restrict__ prob_sum, int32_t* __restrict__ offsets, float* __restrict__ lb_loss,
+    int32_t* __restrict__ perm, int32_t* __restrict__ inv_pos) {
   const int lane = threadIdx.x & (kWave - 1);
+  // lane e: expert e's first grouped row.  capacity: an expert keeps its first `cap` pairs; the
+  // statistics see the routing
+  const int cnt = lane < E ? counts[lane] : 0;
+  const int kept = cap > 0 ? min(cnt, cap) : cnt;
+  int incl = kept;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int u = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += u;
+  }
+  const int group0 = incl - kept;
+  const int kept_total = __shfl(incl, kWave - 1, kWave);
+  if (blockIdx.x == 0 && threadIdx.x < kWave) {
+    if (lane < E) offsets[lane] = group0;
+    if (lane == 0) offsets[E] = kept_total;
+    float term = 0.f;
+    if (lane < E) {
+      const float u = lb_mode == BTX_LB_TOKEN_FRAC ? (float)cnt / ((float)T * (float)k) : gate_sum[lane] / (float)T;
+      term = u * (prob_sum[lane] / (float)T);
+    }
+    float loss = 0.f;
+    for (int e = 0; e < E; ++e) loss += __shfl(term, e, kWave);   // expert order
+    if (lane == 0) *lb_loss = lb_alpha * (float)E * loss;
+  }
+  // grouped rows past the kept ones do not exist; whoever indexes through perm there
+  // (kernels that run over all T*k rows) must still find a valid pair
+  for (int64_t r = (int64_t)kept_total + blockIdx.x * blockDim.x + threadIdx.x; r < (int64_t)T * k;
+       r += (int64_t)gridDim.x * blockDim.x)
+    perm[r] = 0;
+
   const int b = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;  // one wavefront per token block
   if (b >= nblk) return;
   const int first = b * kTokPerBlock * k;
   const int last = min((b + 1) * kTokPerBlock, T) * k;
   // lane e carries the rank, inside expert e's pairs, of the next pair of this block
   int next = lane < E ? blk_base[(size_t)b * E + lane] : 0;
-  const int group0 = lane < E ? offsets[lane] : 0;
   for (int i0 = first; i0 < last; i0 += kWave) {
     const int i = i0 + lane;
     const bool valid = i < last;
@@ -389,35 +372,53 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_scatter_kernel(
   }
 }
 
+// W_router [d,E] -> [E,d]
+__global__ __launch_bounds__(256) void transpose_wr_kernel(const float* __restrict__ Wr, int d, int E,
+                                                           float* __restrict__ WrT) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= d * E) return;
+  const int e = i / d, c = i - e * d;
+  WrT[i] = Wr[(size_t)c * E + e];
+}
+
 template <typename XT>
-void launch_tokens(const RouteArgs& a, int nblk, int32_t* bc, float* bg, float* bp, hipStream_t s) {
+void launch_tokens(const RouteArgs& a, const float* WrT, int nblk, int32_t* bc, float* bg, float* bp, hipStream_t s) {
   const XT* x = static_cast<const XT*>(a.x);
   dim3 grid(nblk), block(kWavesPerBlock * kWave);
 #define BTX_ROUTE_LAUNCH(EC)                                                                                       \
   do {                                                                                                             \
     if (a.gain)                                                                                                    \
       route_tokens_kernel<XT, EC, true><<<grid, block, 0, s>>>(                                                    \
-          x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates,       \
-          a.probs, bc, bg, bp, a.gain, a.eps, static_cast<XT*>(a.xn), a.rstd);                                      \
+          x, WrT, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates, a.probs, bc,  \
+          bg, bp, a.gain, a.eps, static_cast<XT*>(a.xn), a.rstd);                                                   \
     else                                                                                                           \
       route_tokens_kernel<XT, EC, false><<<grid, block, 0, s>>>(                                                   \
-          x, a.W_router, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates,       \
-          a.probs, bc, bg, bp, nullptr, 0.f, nullptr, nullptr);                                                     \
+          x, WrT, a.b_router, a.U, a.T, a.d, a.E, a.k, a.route_mode, 1.f / a.tau, a.topk_idx, a.gates, a.probs, bc,  \
+          bg, bp, nullptr, 0.f, nullptr, nullptr);                                                                  \
   } while (0)
   if (a.E <= 1) BTX_ROUTE_LAUNCH(1);
   else if (a.E <= 2) BTX_ROUTE_LAUNCH(2);
   else if (a.E <= 4) BTX_ROUTE_LAUNCH(4);
-  else BTX_ROUTE_LAUNCH(8);
+  else BTX_ROUTE_LAUNCH(8);   // 16 per pass was measured no faster at E = 32
 #undef BTX_ROUTE_LAUNCH
 }
 
 }  // namespace
 
-static int num_blocks(int T) { return ceil_div(T, kTokPerBlock); }
+int launch_transpose_wr(const float* Wr, int d, int E, float* WrT, hipStream_t s) {
+  transpose_wr_kernel<<<ceil_div(d * E, 256), 256, 0, s>>>(Wr, d, E, WrT);
+  BTX_LAUNCH_CHECK();
+  return BTX_OK;
+}
 
-size_t route_workspace_bytes(int T, int E, int /*k*/) {
+static int num_blocks(int T) { return ceil_div(T, kTokPerBlock); }
+static size_t block_stats_bytes(int T, int E) {
   // block counts, block bases (int32) and block gate/prob sums (fp32)
   return align_up((size_t)num_blocks(T) * E * 4 * sizeof(int32_t), 256);
+}
+
+size_t route_workspace_bytes(int T, int d, int E, int /*k*/) {
+  return block_stats_bytes(T, E) + align_up((size_t)E * d * sizeof(float), 256);   // + W_router transposed
 }
 
 int launch_route(const RouteArgs& a, hipStream_t s) {
@@ -427,14 +428,16 @@ int launch_route(const RouteArgs& a, hipStream_t s) {
   int32_t* bb = bc + n;
   float* bg = reinterpret_cast<float*>(bb + n);
   float* bp = bg + n;
-  if (a.x_dtype == BTX_BF16) launch_tokens<bf16_t>(a, nblk, bc, bg, bp, s);
-  else launch_tokens<float>(a, nblk, bc, bg, bp, s);
+  float* WrT = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + block_stats_bytes(a.T, a.E));
+  if (int rc = launch_transpose_wr(a.W_router, a.d, a.E, WrT, s)) return rc;
+  if (a.x_dtype == BTX_BF16) launch_tokens<bf16_t>(a, WrT, nblk, bc, bg, bp, s);
+  else launch_tokens<float>(a, WrT, nblk, bc, bg, bp, s);
   BTX_LAUNCH_CHECK();
-  route_scan_kernel<<<1, kScanThreads, 0, s>>>(nblk, a.T, a.E, a.k, a.cap, a.lb_mode, a.lb_alpha, bc, bg, bp, bb,
-                                               a.counts, a.offsets, a.gate_sum, a.prob_sum, a.lb_loss, a.perm);
+  route_scan_kernel<<<a.E, kScanThreads, 0, s>>>(nblk, a.E, bc, bg, bp, bb, a.counts, a.gate_sum, a.prob_sum);
   BTX_LAUNCH_CHECK();
   route_scatter_kernel<<<ceil_div(nblk, kWavesPerBlock), kWavesPerBlock * kWave, 0, s>>>(
-      nblk, a.T, a.E, a.k, a.cap, a.topk_idx, bb, a.offsets, a.perm, a.inv_pos);
+      nblk, a.T, a.E, a.k, a.cap, a.lb_mode, a.lb_alpha, a.topk_idx, bb, a.counts, a.gate_sum, a.prob_sum, a.offsets,
+      a.lb_loss, a.perm, a.inv_pos);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }

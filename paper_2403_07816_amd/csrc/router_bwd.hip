@@ -7,14 +7,14 @@
 //   dwr_partial     dW_router = x^T ds as per-token-chunk partial sums
 //   dwr_reduce      fixed-order sum of the partials (and of db_router)
 //   dx_finish       dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T, W_router slice kept in registers
+// dwr_partial and dx_finish work expert-major (partials [chunk][E][d], W_router as [E,d]): a
+// lane's 8 columns of one expert are then 32 contiguous bytes instead of 8 pieces E floats apart.
 #include "common.h"
 
 namespace btx {
 namespace {
 
-constexpr int kTokChunk = 64;   // tokens per dW_router partial
 constexpr int kColsPerThread = 8;
-constexpr int kEC = 8;          // experts per dW_router pass
 
 __global__ __launch_bounds__(256) void router_ds_kernel(
     int T, int E, int k, int mode, int lb_mode, float lb_alpha, float lam, unsigned flags,
@@ -81,83 +81,60 @@ __global__ __launch_bounds__(256) void router_ds_kernel(
   if (live) ds[(size_t)t * E + lane] = dsv;
 }
 
-template <typename XT> struct Ld8;
-template <> struct Ld8<bf16_t> {
-  static __device__ __forceinline__ void ld(const bf16_t* p, float* v) {
-    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
-  }
-  static __device__ __forceinline__ void st(bf16_t* p, const float* v) {
-    u32x4 w;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
-    *reinterpret_cast<u32x4*>(p) = w;
-  }
-};
-template <> struct Ld8<float> {
-  static __device__ __forceinline__ void ld(const float* p, float* v) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
-  }
-  static __device__ __forceinline__ void st(float* p, const float* v) {
-    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
-    *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
-  }
-};
-
-// grid: (token chunks, column blocks of 256*8, expert passes of kEC)
-template <typename XT>
+// grid: (token chunks of CHUNK, column blocks of 256*8, expert passes of KEC).  The partial sums
+// are stored expert-major ([chunk][E][d]): a thread's 8 columns of an expert are 32 contiguous bytes.
+template <typename XT, int KEC, int CHUNK>
 __global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__ x, const float* __restrict__ ds, int T,
                                                           int d, int E, float* __restrict__ part,
                                                           float* __restrict__ db_part) {
-  __shared__ float s_ds[kTokChunk][kEC];
-  const int t0 = blockIdx.x * kTokChunk, e0 = blockIdx.z * kEC;
-  const int nt = min(kTokChunk, T - t0);
-  for (int i = threadIdx.x; i < kTokChunk * kEC; i += 256) {
-    const int q = i / kEC, j = i % kEC;
+  __shared__ float s_ds[CHUNK][KEC];
+  const int t0 = blockIdx.x * CHUNK, e0 = blockIdx.z * KEC;
+  const int nt = min(CHUNK, T - t0);
+  for (int i = threadIdx.x; i < CHUNK * KEC; i += 256) {
+    const int q = i / KEC, j = i % KEC;
     s_ds[q][j] = (q < nt && e0 + j < E) ? ds[(size_t)(t0 + q) * E + e0 + j] : 0.f;
   }
   __syncthreads();
   const int c0 = (blockIdx.y * 256 + threadIdx.x) * kColsPerThread;
   if (c0 < d) {
-    float acc[kColsPerThread][kEC] = {};
+    float acc[KEC][kColsPerThread] = {};
     // 4 token rows in flight; rows past the chunk's end are read from a clamped address and
     // meet the zeros of s_ds
     for (int q = 0; q < nt; q += 4) {
       float xv[4][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) Ld8<XT>::ld(x + (size_t)min(t0 + q + u, T - 1) * d + c0, xv[u]);
+      for (int u = 0; u < 4; ++u) RowVec<XT, 8>::ld(x + (size_t)min(t0 + q + u, T - 1) * d + c0, xv[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int j = 0; j < KEC; ++j) {
+          const float w = s_ds[q + u][j];
 #pragma unroll
-          for (int j = 0; j < kEC; ++j) acc[i][j] = fmaf(xv[u][i], s_ds[q + u][j], acc[i][j]);
+          for (int i = 0; i < 8; ++i) acc[j][i] = fmaf(xv[u][i], w, acc[j][i]);
+        }
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < kEC; ++j)
-        if (e0 + j < E) part[((size_t)blockIdx.x * d + c0 + i) * E + e0 + j] = acc[i][j];
+    for (int j = 0; j < KEC; ++j)
+      if (e0 + j < E) RowVec<float, 8>::st(part + ((size_t)blockIdx.x * E + e0 + j) * d + c0, acc[j]);
   }
-  if (blockIdx.y == 0 && threadIdx.x < kEC && e0 + threadIdx.x < E) {
+  if (blockIdx.y == 0 && threadIdx.x < KEC && e0 + threadIdx.x < E) {
     float a = 0.f;
     for (int q = 0; q < nt; ++q) a += s_ds[q][threadIdx.x];
     db_part[(size_t)blockIdx.x * E + e0 + threadIdx.x] = a;
   }
 }
 
-// 64 outputs per block; 16 thread groups each add every 16th partial, then the 16 sums are added
-// in group order (a fixed order, like everything else here).
+// 64 sums per block, taken in the partials' expert-major order (coalesced reads) and written to
+// dW_router's [d,E] place; 16 thread groups each add every 16th partial, then the 16 sums are
+// added in group order (a fixed order, like everything else here).
 constexpr int kRedGroups = 16;
 __global__ __launch_bounds__(64 * kRedGroups) void dwr_reduce_kernel(const float* __restrict__ part,
                                                                       const float* __restrict__ db_part, int nchunk,
-                                                                      int dE, int E, float* __restrict__ dWr,
+                                                                      int d, int E, float* __restrict__ dWr,
                                                                       float* __restrict__ db) {
   __shared__ float s_sum[kRedGroups][64];
   const int o = threadIdx.x % 64, grp = threadIdx.x / 64;
+  const int dE = d * E;
   const int i = blockIdx.x * 64 + o;
   s_sum[grp][o] = i < dE ? strided_row_sum(part, dE, i, grp, kRedGroups, nchunk) : 0.f;
   __syncthreads();
@@ -165,7 +142,8 @@ __global__ __launch_bounds__(64 * kRedGroups) void dwr_reduce_kernel(const float
     float a = 0.f;
 #pragma unroll
     for (int g = 0; g < kRedGroups; ++g) a += s_sum[g][o];
-    dWr[i] = a;
+    const int e = i / d, c = i - e * d;
+    dWr[(size_t)c * E + e] = a;
   }
   if (db && blockIdx.x == 0 && threadIdx.x < E) {
     float b = 0.f;
@@ -175,52 +153,51 @@ __global__ __launch_bounds__(64 * kRedGroups) void dwr_reduce_kernel(const float
 }
 
 // dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T.  A wavefront owns 512 columns (8 per lane)
-// for kDxTok tokens, 4 of them in flight at a time; its slice of W_router ([d,E] fp32) stays in
-// registers when E <= EC, so the kernel streams dxs and dX and little else.
-constexpr int kDxTok = 16;
-template <typename XT, int EC>
+// for TOK tokens, 4 of them in flight at a time; its slice of W_router (read from the [E,d]
+// copy) stays in registers when E <= EC, so the kernel streams dxs and dX and little else.
+// With more experts the slice is reloaded in pieces of EC per 4 tokens (cache hits): 4 columns
+// per lane with the whole slice resident was measured slower (8-byte row loads).
+template <typename XT, int EC, int TOK>
 __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ dxs, const int32_t* __restrict__ inv_pos,
-                                                        const float* __restrict__ ds, const float* __restrict__ Wr,
+                                                        const float* __restrict__ ds, const float* __restrict__ WrT,
                                                         int T, int d, int E, int k, XT* __restrict__ dX) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int c0 = ((blockIdx.y * 4 + wave) * kWave + lane) * 8;
-  const int t0 = blockIdx.x * kDxTok;
+  const int t0 = blockIdx.x * TOK;
   if (c0 >= d) return;                      // no cross-lane traffic below
   const int n_ch = (E + EC - 1) / EC;
-  float wr[8][EC];
+  float wr[EC][8];
   auto load_wr = [&](int e0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float* row = Wr + (size_t)(c0 + i) * E + e0;
-      if (E % 4 == 0) {                     // whole 16-byte groups, aligned
-#pragma unroll
-        for (int v = 0; v < EC / 4; ++v) {
-          f32x4 w4{0.f, 0.f, 0.f, 0.f};
-          if (e0 + 4 * v < E) w4 = *reinterpret_cast<const f32x4*>(row + 4 * v);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) wr[i][4 * v + j] = w4[j];
-        }
+    for (int j = 0; j < EC; ++j) {
+      if (e0 + j < E) {
+        RowVec<float, 8>::ld(WrT + (size_t)(e0 + j) * d + c0, wr[j]);
       } else {
 #pragma unroll
-        for (int j = 0; j < EC; ++j) wr[i][j] = e0 + j < E ? row[j] : 0.f;
+        for (int i = 0; i < 8; ++i) wr[j][i] = 0.f;
       }
     }
   };
   if (n_ch == 1) load_wr(0);
-  for (int tq = 0; tq < kDxTok; tq += 4) {
+  for (int tq = 0; tq < TOK; tq += 4) {
     float acc[4][8] = {};
+    // slot by slot, the four tokens' rows in flight together; a dropped pair (or a token past
+    // the end) reads row 0 and adds zero
+#pragma unroll 2
+    for (int j = 0; j < k; ++j) {
+      float v[4][8];
+      bool have[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int t = t0 + tq + q;
-      if (t >= T) break;
-      for (int j = 0; j < k; ++j) {
-        const int r = inv_pos[(size_t)t * k + j];
-        if (r < 0) continue;
-        float v[8];
-        Ld8<XT>::ld(dxs + (size_t)r * d + c0, v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[q][i] += v[i];
+      for (int q = 0; q < 4; ++q) {
+        const int t = t0 + tq + q;
+        const int r = t < T ? inv_pos[(size_t)t * k + j] : -1;
+        have[q] = r >= 0;
+        RowVec<XT, 8>::ld(dxs + (size_t)max(r, 0) * d + c0, v[q]);
       }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[q][i] += have[q] ? v[q][i] : 0.f;
     }
     for (int ch = 0; ch < n_ch; ++ch) {
       if (n_ch > 1) load_wr(ch * EC);
@@ -233,58 +210,76 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ d
           const int e = ch * EC + j;
           const float w = e < E ? ds[(size_t)t * E + e] : 0.f;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc[q][i] = fmaf(w, wr[i][j], acc[q][i]);
+          for (int i = 0; i < 8; ++i) acc[q][i] = fmaf(w, wr[j][i], acc[q][i]);
         }
       }
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (t0 + tq + q < T) Ld8<XT>::st(dX + (size_t)(t0 + tq + q) * d + c0, acc[q]);
+      if (t0 + tq + q < T) RowVec<XT, 8>::st(dX + (size_t)(t0 + tq + q) * d + c0, acc[q]);
   }
 }
 
 }  // namespace
 
-static int n_chunks(int T) { return ceil_div(T, kTokChunk); }
+// token chunk of the dW_router partial sums: longer chunks for many experts keep the partials
+// (chunks * d * E floats) small next to x
+static int tok_chunk(int E) { return E <= 8 ? 64 : 128; }
+static int n_chunks(int T, int E) { return ceil_div(T, tok_chunk(E)); }
 
 size_t router_bwd_workspace_bytes(int T, int d, int E) {
   const size_t ds = align_up((size_t)T * E * sizeof(float), 256);
-  const size_t part = align_up((size_t)n_chunks(T) * d * E * sizeof(float), 256);
-  const size_t dbp = align_up((size_t)n_chunks(T) * E * sizeof(float), 256);
-  return ds + part + dbp;
+  const size_t part = align_up((size_t)n_chunks(T, E) * d * E * sizeof(float), 256);
+  const size_t dbp = align_up((size_t)n_chunks(T, E) * E * sizeof(float), 256);
+  const size_t wrt = align_up((size_t)E * d * sizeof(float), 256);
+  return ds + part + dbp + wrt;
 }
 
 int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
+  const int nch = n_chunks(a.T, a.E);
   char* w = static_cast<char*>(a.workspace);
   float* ds = reinterpret_cast<float*>(w);
   w += align_up((size_t)a.T * a.E * sizeof(float), 256);
   float* part = reinterpret_cast<float*>(w);
-  w += align_up((size_t)n_chunks(a.T) * a.d * a.E * sizeof(float), 256);
+  w += align_up((size_t)nch * a.d * a.E * sizeof(float), 256);
   float* dbp = reinterpret_cast<float*>(w);
+  w += align_up((size_t)nch * a.E * sizeof(float), 256);
+  float* WrT = reinterpret_cast<float*>(w);
 
+  if (int rc = launch_transpose_wr(a.W_router, a.d, a.E, WrT, s)) return rc;
   router_ds_kernel<<<ceil_div(a.T, 4), 256, 0, s>>>(a.T, a.E, a.k, a.route_mode, a.lb_mode, a.lb_alpha, a.lb_grad_scale,
                                                    a.flags, a.noise, a.noise ? 1.f / a.tau : 1.f, a.topk_idx, a.gates,
                                                    a.probs, a.inv_pos, a.gate_sum,
                                                    a.prob_sum, a.counts, a.dg_part, a.n_part, ds);
   BTX_LAUNCH_CHECK();
-  dim3 grid(n_chunks(a.T), ceil_div(a.d, 256 * kColsPerThread), ceil_div(a.E, kEC));
-  if (a.dtype == BTX_BF16)
-    dwr_partial_kernel<bf16_t><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(a.x), ds, a.T, a.d, a.E, part, dbp);
-  else
-    dwr_partial_kernel<float><<<grid, 256, 0, s>>>(static_cast<const float*>(a.x), ds, a.T, a.d, a.E, part, dbp);
+  auto typed = [&](auto tag) {
+    using XT = decltype(tag);
+    const XT* x = static_cast<const XT*>(a.x);
+    const int col_blocks = ceil_div(a.d, 256 * kColsPerThread);
+    if (a.E <= 8)
+      dwr_partial_kernel<XT, 8, 64><<<dim3(nch, col_blocks, 1), 256, 0, s>>>(x, ds, a.T, a.d, a.E, part, dbp);
+    else
+      dwr_partial_kernel<XT, 16, 128><<<dim3(nch, col_blocks, ceil_div(a.E, 16)), 256, 0, s>>>(x, ds, a.T, a.d, a.E,
+                                                                                             part, dbp);
+  };
+  if (a.dtype == BTX_BF16) typed(bf16_t{});
+  else typed(float{});
   BTX_LAUNCH_CHECK();
-  dwr_reduce_kernel<<<ceil_div((int64_t)a.d * a.E, 64), 64 * kRedGroups, 0, s>>>(part, dbp, n_chunks(a.T), a.d * a.E,
-                                                                                 a.E, a.dW_router, a.db_router);
+  dwr_reduce_kernel<<<ceil_div(a.d * a.E, 64), 64 * kRedGroups, 0, s>>>(part, dbp, nch, a.d, a.E, a.dW_router,
+                                                                       a.db_router);
   BTX_LAUNCH_CHECK();
-  const dim3 dx_grid(ceil_div(a.T, kDxTok), ceil_div(a.d, 4 * kWave * 8));
   auto dx_launch = [&](auto tag) {
     using XT = decltype(tag);
     const XT* dxs = static_cast<const XT*>(a.dxs);
     XT* dX = static_cast<XT*>(a.dX);
-    if (a.E <= 4)
-      dx_finish_kernel<XT, 4><<<dx_grid, 256, 0, s>>>(dxs, a.inv_pos, ds, a.W_router, a.T, a.d, a.E, a.k, dX);
-    else
-      dx_finish_kernel<XT, 8><<<dx_grid, 256, 0, s>>>(dxs, a.inv_pos, ds, a.W_router, a.T, a.d, a.E, a.k, dX);
+#define BTX_DX_LAUNCH(EC, TOK)                                                                                       \
+  dx_finish_kernel<XT, EC, TOK><<<dim3(ceil_div(a.T, TOK), ceil_div(a.d, 4 * kWave * 8)), 256, 0, s>>>(dxs, a.inv_pos, \
+                                                                                                      ds, WrT, a.T, a.d, \
+                                                                                                      a.E, a.k, dX)
+    if (a.E <= 4) BTX_DX_LAUNCH(4, 16);
+    else if (a.E <= 8) BTX_DX_LAUNCH(8, 16);
+    else BTX_DX_LAUNCH(16, 32);
+#undef BTX_DX_LAUNCH
   };
   if (a.dtype == BTX_BF16) dx_launch(bf16_t{});
   else dx_launch(float{});

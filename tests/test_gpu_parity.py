@@ -357,7 +357,7 @@ def test_layer_step_replays_from_a_hip_graph():
     saved = (torch.empty((T * k, f), dtype=BF16, device="cuda"), torch.empty((T * k, f), dtype=BF16, device="cuda"))
     grads = B.Grads(torch.empty_like(L["x"]), torch.empty((d, E), device="cuda"), torch.empty(E, device="cuda"),
                     torch.empty_like(L["W1"]), torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
-    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, E, k),
+    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, d, E, k),
                          lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
                          lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16)), dtype=torch.uint8,
                      device="cuda")
@@ -402,7 +402,7 @@ def test_block_step_replays_from_a_hip_graph():
     saved = (torch.empty((T * k, f), dtype=BF16, device="cuda"), torch.empty((T * k, f), dtype=BF16, device="cuda"))
     grads = B.Grads(torch.empty_like(h), torch.empty((d, E), device="cuda"), torch.empty(E, device="cuda"),
                     torch.empty_like(L["W1"]), torch.empty_like(L["W3"]), torch.empty_like(L["W2"]))
-    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, E, k),
+    ws = torch.empty(max(lib.btx_moe_route_workspace_bytes(T, d, E, k),
                          lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
                          lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, B.BTX_BF16),
                          lib.btx_rmsnorm_backward_workspace_bytes(T, d)), dtype=torch.uint8, device="cuda")
