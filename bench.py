@@ -32,7 +32,7 @@ WORKLOAD = dict(name="llama2-7b-shaped MoE-FF layer, fwd+bwd, T=16384 (4 seq x 4
                 T=16384, d=4096, f=11008, E=4, k=2, alpha=0.01)
 # FETCH_SIZE / WRITE_SIZE read this fraction of the known traffic of a plain streaming kernel (combine_kernel;
 # see profiles/layer_fwd_bwd_c2_pmc_counters.txt): 128-byte reads are counted as 64 bytes on this chip
-FETCH_FACTOR, WRITE_FACTOR = 0.5027, 1.000
+FETCH_FACTOR, WRITE_FACTOR = 0.5028, 1.000
 # routing variants that can be timed; top2 is the benchmark configuration
 VARIANTS = {
     "top2": dict(name="top-2", k=2, mode=0, bias=None, tau=1.0, cf=0.0),
