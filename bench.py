@@ -46,6 +46,8 @@ VARIANTS = {
     # 4 FFs split into 8 chunks each (Sec. 3.3 "Splitting Experts"): 32 experts of width 1376, top-8
     "split8-top8": dict(name="32 split experts of width 1376, top-8", k=8, mode=0, bias=None, tau=1.0, cf=0.0, E=32,
                         f=1376),
+    # inference: router and forward only, nothing kept for a backward pass
+    "forward": dict(name="top-2, forward only", k=2, mode=0, bias=None, tau=1.0, cf=0.0, forward_only=True),
 }
 GEMM_STAGES = {"up_swiglu": 4, "down": 2, "bwd_act": 2, "bwd_dx": 4, "dw13": 4, "dw2": 2}   # x d*f*R flops
 
@@ -249,6 +251,9 @@ def main():
             return
         B.btx_moe_route(L["x"], L["W_router"], L["b_router"], noise, k, V["mode"], B.BTX_LB_TOKEN_FRAC, alpha,
                         out=routing, workspace=ws, tau=V["tau"], capacity_factor=V["cf"])
+        if V.get("forward_only"):
+            B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, save=False, out=out, workspace=ws)
+            return
         B.btx_moe_ff_forward(L["x"], L["W1"], L["W3"], L["W2"], routing, save=True, out=out, saved=saved, workspace=ws)
         B.btx_moe_ff_backward(L["dY"], L["x"], L["W_router"], L["W1"], L["W3"], L["W2"], routing, saved[0], saved[1],
                               V["mode"], B.BTX_LB_TOKEN_FRAC, alpha, 1.0, 0, out=grads, workspace=ws, noise=noise,
@@ -278,20 +283,24 @@ def main():
         v = [events.elapsed_ms(2 * n_stage * s + 2 * i, 2 * n_stage * s + 2 * i + 1) for s in range(args.steps)]
         stage_ms[name] = float(np.mean(v))
     R = int(routing.offsets[-1].item())     # grouped rows the expert GEMMs worked on (T*k unless pairs were dropped)
-    gemm = {n: {"ms": stage_ms[n], "tflops": c * d * f * R / (stage_ms[n] * 1e-3) / 1e12} for n, c in GEMM_STAGES.items()}
+    gemm = {n: {"ms": stage_ms[n], "tflops": c * d * f * R / (stage_ms[n] * 1e-3) / 1e12}
+            for n, c in GEMM_STAGES.items() if stage_ms[n] > 0}
+    gemm_coef = float(sum(GEMM_STAGES[n] for n in gemm))    # 18 for forward + backward
     dominant = max(gemm, key=lambda n: gemm[n]["ms"])
     gemm_ms = sum(v["ms"] for v in gemm.values())
-    gemm_tflops = 18.0 * d * f * R / (gemm_ms * 1e-3) / 1e12
+    gemm_tflops = gemm_coef * d * f * R / (gemm_ms * 1e-3) / 1e12
 
     ms_per_step = elapsed / args.steps * 1e3
     sustained = sustained_mfma_tflops(L["x"])
     result = {
-        "metric": "MoE-FF layer tokens/s fwd+bwd (d4096,f11008,E4,top2)",
+        "metric": "MoE-FF layer tokens/s fwd+bwd (d4096,f11008,E4,top2)" if not V.get("forward_only")
+                  else "MoE-FF layer tokens/s forward only (d4096,f11008,E4,top2)",
         "value": T * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": (W["name"] if args.variant == "top2" else
-                                W["name"].replace("top-2", V["name"]).replace("f=11008, E=4, ", "" if "E" in V else "f=11008, E=4, "))
+                                W["name"].replace("top-2", V["name"]).replace("f=11008, E=4, ", "" if "E" in V else "f=11008, E=4, ")
+                                .replace("fwd+bwd, " if V.get("forward_only") else "\0", ""))
                    if T == WORKLOAD["T"] else f"dev run, T={T}, {V['name']}", "tokens": T, "routed_rows": R, "d_model": d,
                    "d_ff": f, "experts": E, "top_k": k},
         "roofline": {"bound": "mfma", "kernel": f"mfma_gemm_kernel ({dominant})", "achieved": gemm[dominant]["tflops"],
@@ -302,7 +311,7 @@ def main():
                      "sustained_mfma_peak": sustained, "frac_of_sustained": gemm[dominant]["tflops"] / sustained},
         "expert_gemms": {"ms": gemm_ms, "tflops": gemm_tflops, "frac_of_peak": gemm_tflops / PEAK_BF16_TFLOPS,
                          "frac_of_sustained": gemm_tflops / sustained,
-                         "layer_frac_of_peak": 18.0 * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                         "layer_frac_of_peak": gemm_coef * d * f * R / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                          "per_kernel": gemm},
         "stage_ms": stage_ms,
         "step_ms": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},

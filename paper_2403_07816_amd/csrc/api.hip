@@ -22,7 +22,7 @@ inline int esize(int dtype) { return dtype == BTX_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dtype) { return dtype == BTX_F32 || dtype == BTX_BF16; }
 
 struct FwdWs { void *xs, *act, *y, *h1, *h3; size_t bytes; };
-FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype) {
+FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype, bool save) {
   const size_t R = (size_t)T * k, es = esize(dtype);
   Carver c(ws);
   FwdWs w;
@@ -30,8 +30,10 @@ FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype) {
   w.xs = ff_gather_fused(dtype, T, d, f) ? nullptr : c.take(R * d * es);
   w.act = c.take(R * f * es);
   w.y = c.take(R * d * es);
-  w.h1 = c.take(R * f * es);  // used only when the caller does not keep h1/h3
-  w.h3 = c.take(R * f * es);
+  // h1/h3 when the caller does not keep them: only the plain path needs them at all
+  const bool own_h = !save && ff_up_needs_h(dtype, d, f);
+  w.h1 = own_h ? c.take(R * f * es) : nullptr;
+  w.h3 = own_h ? c.take(R * f * es) : nullptr;
   w.bytes = c.used;
   return w;
 }
@@ -188,7 +190,7 @@ int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, cons
 
 size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int dtype) {
   if (!dtype_ok(dtype) || !shapes_ok(T, d, f, E, k) || T == 0) return 0;
-  return carve_forward(nullptr, T, d, f, k, dtype).bytes;
+  return carve_forward(nullptr, T, d, f, k, dtype, /*save=*/false).bytes;   // the larger of the two cases
 }
 
 int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,
@@ -202,7 +204,7 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   if (T == 0) return BTX_OK;
   if (!x || !W1 || !W3 || !W2 || !gates || !offsets || !perm || !inv_pos || !out || !workspace)
     return BTX_ERR_INVALID_ARG;
-  const FwdWs w = carve_forward(workspace, T, d, f, k, dtype);
+  const FwdWs w = carve_forward(workspace, T, d, f, k, dtype, save_h1 != nullptr);
   if (workspace_bytes < w.bytes) return BTX_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int R = T * k;

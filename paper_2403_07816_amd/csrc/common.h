@@ -209,7 +209,9 @@ struct FfShapes { int R, d, f, E; int64_t s13, s2; };
 // stages of a problem read token rows through perm themselves.
 struct RowSource { const void* base; const int32_t* perm; int k; };
 bool ff_gather_fused(int dtype, int T, int d, int f);
-// a = silu(xs W1) * (xs W3); h1/h3 stored when non-null
+// a = silu(xs W1) * (xs W3); h1/h3 stored when non-null.  They may be null only when
+// ff_up_needs_h() is false: the plain path computes act from the stored h1/h3.
+bool ff_up_needs_h(int dtype, int d, int f);
 int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* scratch, hipStream_t s);
 // y = act W2

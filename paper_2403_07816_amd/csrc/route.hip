@@ -406,6 +406,7 @@ void launch_tokens(const RouteArgs& a, const float* WrT, int nblk, int32_t* bc, 
 }  // namespace
 
 int launch_transpose_wr(const float* Wr, int d, int E, float* WrT, hipStream_t s) {
+  if ((int64_t)d * E >= (int64_t)1 << 31) return BTX_ERR_UNSUPPORTED;   // the kernels index W_router with 32 bits
   transpose_wr_kernel<<<ceil_div(d * E, 256), 256, 0, s>>>(Wr, d, E, WrT);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
