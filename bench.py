@@ -46,6 +46,8 @@ VARIANTS = {
     # 4 FFs split into 8 chunks each (Sec. 3.3 "Splitting Experts"): 32 experts of width 1376, top-8
     "split8-top8": dict(name="32 split experts of width 1376, top-8", k=8, mode=0, bias=None, tau=1.0, cf=0.0, E=32,
                         f=1376),
+    # soft routing (Sec. 3.3): every expert active, gates = softmax; the same path with k = E
+    "soft": dict(name="soft routing (top-4 of 4)", k=4, mode=0, bias=None, tau=1.0, cf=0.0),
     # inference: router and forward only, nothing kept for a backward pass
     "forward": dict(name="top-2, forward only", k=2, mode=0, bias=None, tau=1.0, cf=0.0, forward_only=True),
 }
