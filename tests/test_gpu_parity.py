@@ -27,7 +27,10 @@ def test_config0_shape_fp32_forward_backward():
 
 
 @pytest.mark.parametrize("T,d,f,E,k", [(301, 72, 88, 5, 3), (1, 64, 64, 4, 2), (67, 136, 200, 7, 7), (130, 64, 40, 32, 8),
-                                       (1000, 128, 64, 64, 4), (17, 8, 8, 1, 1)])
+                                       (1000, 128, 64, 64, 4), (17, 8, 8, 1, 1),
+                                       # expert counts that leave the last register chunk of the router kernels
+                                       # partly empty (8 per pass forward, 16 in the backward)
+                                       (45, 64, 64, 33, 5), (300, 128, 96, 17, 3), (257, 72, 40, 9, 9)])
 def test_ragged_shapes_fp32(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, F32)
 
@@ -87,6 +90,12 @@ def test_capacity_factor_drops_pairs_in_token_order_fp32(mode, k, cf, bias):
     dropped = int((r.inv_pos < 0).sum())
     assert (dropped > 0) == (cf < 4.0)
     assert int(r.offsets[-1]) == 301 * k - dropped
+
+
+def test_capacity_factor_with_many_experts_fp32():
+    """Dropped pairs where the router backward reloads its W_router slice in chunks (E > 16)."""
+    G, r, out, g = run_layer_and_check(400, 64, 64, 24, 4, F32, cf=0.5, bias=[1.0] * 4 + [0.0] * 20)
+    assert int((r.inv_pos < 0).sum()) > 0
 
 
 def test_capacity_factor_gate_mean_statistics_fp32():
@@ -174,7 +183,8 @@ def test_empty_batch_is_a_noop():
                                        (40, 64, 72, 4, 1),
                                        # MFMA path at its edges: fewer rows than one k tile, many (mostly tiny or
                                        # empty) experts, d and f that are multiples of 32 but not of 64
-                                       (5, 64, 64, 4, 2), (700, 96, 160, 64, 8), (257, 320, 96, 3, 3)])
+                                       (5, 64, 64, 4, 2), (700, 96, 160, 64, 8), (257, 320, 96, 3, 3),
+                                       (300, 128, 96, 17, 3)])
 def test_bf16_forward_backward(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True)
 
