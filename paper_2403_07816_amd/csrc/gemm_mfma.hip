@@ -104,6 +104,18 @@ __device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
   return (uint32_t)(r * ROWB + ((chunk ^ (((r / RP) * STEP) & (CPR - 1))) << 4));
 }
 
+// The 8-byte pieces that the lanes of a fragment write into (and read from) a staged band would
+// meet two-way in the banks: rows r and r+1 (128-byte rows) or r and r+2 (64-byte rows) of a band
+// put the same chunk in the same banks.  Those rows keep the two halves of every 16-byte chunk
+// swapped, so that 16 lanes cover all 32 banks; whoever moves whole chunks swaps them back.
+template <int ROWB, int ES>
+__device__ __forceinline__ uint32_t half_flip(int r) {
+  return ES == 2 ? (uint32_t)(((r >> (ROWB >= 128 ? 0 : 1)) & 1) << 3) : 0u;
+}
+__device__ __forceinline__ u32x4 swap_halves(u32x4 v, bool yes) {
+  return yes ? u32x4{v[2], v[3], v[0], v[1]} : v;
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 struct Gemm {
   // K index contiguous in memory?  A always is.  In the dW products K is the grouped-row index:
@@ -445,7 +457,7 @@ struct Gemm {
     auto piece = [&](auto rowb_tag, auto es_tag, int i2, int j) {
       constexpr int ROWB = decltype(rowb_tag)::value, ES = decltype(es_tag)::value;
       const int byte = (j * 16 + 4 * lane_c) * ES;
-      return stage_off<ROWB, 4 * ES>(i2 * 16 + lane_m, byte >> 4) + (byte & 15);
+      return stage_off<ROWB, 4 * ES>(i2 * 16 + lane_m, byte >> 4) + ((byte & 15) ^ half_flip<ROWB, ES>(i2 * 16 + lane_m));
     };
     float dg_acc[TM];
 #pragma unroll
@@ -481,8 +493,9 @@ struct Gemm {
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
           const uint32_t o = stage_off<ROWB, 8>(t * RPI + cr, cc);
-          *reinterpret_cast<u32x4*>(bufA + o) = p1[t];
-          *reinterpret_cast<u32x4*>(bufB + o) = p3[t];
+          const bool fl = half_flip<ROWB, 2>(t * RPI + cr) != 0;
+          *reinterpret_cast<u32x4*>(bufA + o) = swap_halves(p1[t], fl);
+          *reinterpret_cast<u32x4*>(bufB + o) = swap_halves(p3[t], fl);
         }
         const float gate2[2] = {gate_next[0], gate_next[1]};
         if (ib + 1 < NB) fetch(ib + 1);               // in flight during the arithmetic below
@@ -521,8 +534,9 @@ struct Gemm {
         for (int t = 0; t < NI; ++t) {
           const int r = t * RPI + cr;
           const uint32_t o = stage_off<ROWB, 8>(r, cc);
-          const u32x4 v1 = *reinterpret_cast<const u32x4*>(bufA + o);
-          const u32x4 v3 = *reinterpret_cast<const u32x4*>(bufB + o);
+          const bool fl = half_flip<ROWB, 2>(r) != 0;
+          const u32x4 v1 = swap_halves(*reinterpret_cast<const u32x4*>(bufA + o), fl);
+          const u32x4 v3 = swap_halves(*reinterpret_cast<const u32x4*>(bufB + o), fl);
           if (mb + r < row_end && cn < g.N) {
             const size_t idx = (size_t)(mb + r) * g.ldc + cn;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = v1;
@@ -549,8 +563,9 @@ struct Gemm {
             bf16x8 v[TNH];
 #pragma unroll
             for (int pr = 0; pr < TNH; ++pr) {
-              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
-              const uint32_t o_hi = stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + ((8 * (fa4 & 1)) ^ half_flip<ROWB, 2>(fr));
+              const uint32_t o_hi =
+                  stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + ((8 * (fa4 & 1)) ^ half_flip<ROWB, 2>(fr + 4));
               const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_lo));
               const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_hi));
               v[pr] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -623,7 +638,9 @@ struct Gemm {
 #pragma unroll
             for (int t = 0; t < NI; ++t) {
               const int r = t * RPI + cr;
-              const u32x4 val = *reinterpret_cast<const u32x4*>(wb + pp * (32 * ROWB) + stage_off<ROWB, 4 * ES>(r, cc));
+              const u32x4 val = swap_halves(
+                  *reinterpret_cast<const u32x4*>(wb + pp * (32 * ROWB) + stage_off<ROWB, 4 * ES>(r, cc)),
+                  half_flip<ROWB, ES>(r) != 0);
               if (mb + r < row_end && cn < g.N) *reinterpret_cast<u32x4*>(C + (size_t)(mb + r) * g.ldc + cn) = val;
             }
           }
