@@ -108,6 +108,8 @@ __device__ __forceinline__ uint32_t stage_off(int r, int chunk) {
 // meet two-way in the banks: rows r and r+1 (128-byte rows) or r and r+2 (64-byte rows) of a band
 // put the same chunk in the same banks.  Those rows keep the two halves of every 16-byte chunk
 // swapped, so that 16 lanes cover all 32 banks; whoever moves whole chunks swaps them back.
+// BWD_ACT does without: its epilogue is bound by its vector arithmetic (about 3000 instructions
+// per wavefront), the swaps would add 256 selects to it and its LDS conflicts cost no time.
 template <int ROWB, int ES>
 __device__ __forceinline__ uint32_t half_flip(int r) {
   return ES == 2 ? (uint32_t)(((r >> (ROWB >= 128 ? 0 : 1)) & 1) << 3) : 0u;
@@ -457,7 +459,8 @@ struct Gemm {
     auto piece = [&](auto rowb_tag, auto es_tag, int i2, int j) {
       constexpr int ROWB = decltype(rowb_tag)::value, ES = decltype(es_tag)::value;
       const int byte = (j * 16 + 4 * lane_c) * ES;
-      return stage_off<ROWB, 4 * ES>(i2 * 16 + lane_m, byte >> 4) + ((byte & 15) ^ half_flip<ROWB, ES>(i2 * 16 + lane_m));
+      const uint32_t flip = MODE == BWD_ACT ? 0u : half_flip<ROWB, ES>(i2 * 16 + lane_m);
+      return stage_off<ROWB, 4 * ES>(i2 * 16 + lane_m, byte >> 4) + ((byte & 15) ^ flip);
     };
     float dg_acc[TM];
 #pragma unroll
@@ -493,9 +496,8 @@ struct Gemm {
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
           const uint32_t o = stage_off<ROWB, 8>(t * RPI + cr, cc);
-          const bool fl = half_flip<ROWB, 2>(t * RPI + cr) != 0;
-          *reinterpret_cast<u32x4*>(bufA + o) = swap_halves(p1[t], fl);
-          *reinterpret_cast<u32x4*>(bufB + o) = swap_halves(p3[t], fl);
+          *reinterpret_cast<u32x4*>(bufA + o) = p1[t];
+          *reinterpret_cast<u32x4*>(bufB + o) = p3[t];
         }
         const float gate2[2] = {gate_next[0], gate_next[1]};
         if (ib + 1 < NB) fetch(ib + 1);               // in flight during the arithmetic below
@@ -519,7 +521,7 @@ struct Gemm {
               const float a = sl * v3[x];
               dot = fmaf(dd, a, dot);
               const float da = gate * dd;
-              o1[x] = da * v3[x] * (sg * (1.f + z[x] * (1.f - sg)));
+              o1[x] = da * v3[x] * fmaf(sl, 1.f - sg, sg);     // silu'(z) = sg + silu(z) (1 - sg)
               o3[x] = da * sl;
               oa[x] = gate * a;
             }
@@ -534,9 +536,8 @@ struct Gemm {
         for (int t = 0; t < NI; ++t) {
           const int r = t * RPI + cr;
           const uint32_t o = stage_off<ROWB, 8>(r, cc);
-          const bool fl = half_flip<ROWB, 2>(r) != 0;
-          const u32x4 v1 = swap_halves(*reinterpret_cast<const u32x4*>(bufA + o), fl);
-          const u32x4 v3 = swap_halves(*reinterpret_cast<const u32x4*>(bufB + o), fl);
+          const u32x4 v1 = *reinterpret_cast<const u32x4*>(bufA + o);
+          const u32x4 v3 = *reinterpret_cast<const u32x4*>(bufB + o);
           if (mb + r < row_end && cn < g.N) {
             const size_t idx = (size_t)(mb + r) * g.ldc + cn;
             *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(g.C0) + idx) = v1;
@@ -563,9 +564,8 @@ struct Gemm {
             bf16x8 v[TNH];
 #pragma unroll
             for (int pr = 0; pr < TNH; ++pr) {
-              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + ((8 * (fa4 & 1)) ^ half_flip<ROWB, 2>(fr));
-              const uint32_t o_hi =
-                  stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + ((8 * (fa4 & 1)) ^ half_flip<ROWB, 2>(fr + 4));
+              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+              const uint32_t o_hi = stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
               const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_lo));
               const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_hi));
               v[pr] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
