@@ -13,7 +13,10 @@
  *     f = feed-forward width per expert, E = experts, k = experts per token,
  *     R = T*k routed rows.
  *   - The caller owns every buffer, including the workspace; the library
- *     allocates nothing and keeps no state between calls.
+ *     allocates nothing.  No result depends on an earlier call.  The only
+ *     process-wide state is set-up and tooling: per device, the kernels'
+ *     raised dynamic-LDS limit (btx_init) and the optional stage-event table
+ *     (btx_profile_stages).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and the call returns without synchronising.  Group sizes
  *     never travel to the host.
@@ -77,6 +80,14 @@ typedef enum {
 const char* btx_status_string(int status);
 int btx_version(void);
 
+/* One-time set-up on the CURRENT device: raises the dynamic-LDS limit of every expert-GEMM
+ * kernel (they use all 160 KB of a compute unit's LDS).  Optional: the first bf16 call of
+ * btx_moe_ff_forward / btx_moe_ff_backward on a device does the same by itself, but that
+ * set-up cannot be recorded into a HIP graph, so a caller that captures its very first step
+ * calls btx_init() before beginning the capture (once per device that it uses).
+ * Idempotent.  Errors: BTX_ERR_HIP. */
+int btx_init(void);
+
 /* Profiling aid (the one piece of process-wide state; not thread-safe; off by default).
  * events: HOST array of 2*n_pairs hipEvent_t handles owned by the caller.  While set,
  * stage s of any later call records events[2s] before and events[2s+1] after its
@@ -99,18 +110,6 @@ enum {
   BTX_STAGE_COUNT = 13
 };
 int btx_profile_stages(void** events, int n_pairs);
-
-/* Measurement aid, not part of the method: the rate the matrix cores sustain when fed from
- * registers only.  n_blocks workgroups of 8 wavefronts each run `iters` rounds of 128
- * v_mfma_f32_16x16x32_bf16 (the instruction of the expert GEMMs) whose operands (16 fragments per lane, all pairs) are read once
- * from `data` (DEVICE, 16-byte aligned, data_bytes >= 16, any bf16 values: use the kind of
- * data the layer sees, the chip's clock under load depends on it).  out: DEVICE,
- * btx_probe_mfma_out_bytes(n_blocks) bytes, overwritten with meaningless sums.  *flops (HOST,
- * may be NULL) receives the floating-point operations of the launch; time the launch on
- * `stream` yourself.  Errors: BTX_ERR_INVALID_ARG, BTX_ERR_HIP. */
-size_t btx_probe_mfma_out_bytes(int n_blocks);
-int btx_probe_mfma(const void* data, size_t data_bytes, float* out, int n_blocks, int iters, double* flops,
-                   void* stream);
 
 /* ---------------------------------------------------------------------------
  * btx_moe_route - router linear, softmax, selection, gates, load-balancing
@@ -220,6 +219,10 @@ int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, cons
  * activation silu(h1)*h3 and the expert output are rounded to bf16 once each.
  * dtype BTX_F32: plain fp32 FMA kernels (parity path, not the fast path).
  * Requirements: d % 8 == 0, f % 8 == 0, strides >= d*f.
+ * Limits (BTX_ERR_UNSUPPORTED beyond them; also for btx_moe_ff_backward): the bf16 kernels (d and f
+ * multiples of 32, both >= 64) address the padded grouped rows with 32-bit byte offsets,
+ * ceil(R/64)*64 + 64*E < 2^23 (about 8.3 M routed rows); the plain kernels (fp32, or bf16 with other
+ * d, f) take R/64 + E <= 65535 row tiles (about 4.1 M routed rows).
  */
 size_t btx_moe_ff_forward_workspace_bytes(int T, int d, int f, int E, int k, int dtype);
 int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void* W2, int dtype,

@@ -29,8 +29,7 @@ _SIGNATURES = {
     "btx_status_string": (ctypes.c_char_p, [_i]),
     "btx_version": (_i, []),
     "btx_profile_stages": (_i, [ctypes.POINTER(_vp), _i]),
-    "btx_probe_mfma_out_bytes": (_sz, [_i]),
-    "btx_probe_mfma": (_i, [_vp, _sz, _vp, _i, _i, ctypes.POINTER(ctypes.c_double), _vp]),
+    "btx_init": (_i, []),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
     "btx_moe_norm_route": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 +
@@ -285,16 +284,9 @@ def btx_merge_weighted(tensors: Sequence[torch.Tensor], weights: Sequence[float]
     return out
 
 
-def btx_probe_mfma(data: torch.Tensor, n_blocks: int = 256, iters: int = 1000) -> float:
-    """Launch the register-fed MFMA loop on the current stream; returns its FLOP count
-    (the caller times it)."""
-    lib = load_library()
-    out = torch.empty(lib.btx_probe_mfma_out_bytes(n_blocks) // 4, dtype=torch.float32, device=data.device)
-    flops = ctypes.c_double()
-    st = lib.btx_probe_mfma(_ptr(data), data.numel() * data.element_size(), _ptr(out), n_blocks, iters,
-                            ctypes.byref(flops), _stream())
-    _check(st, "btx_probe_mfma")
-    return flops.value
+def btx_init() -> None:
+    """One-time set-up of the library on the current device (see btx_moe.h)."""
+    _check(load_library().btx_init(), "btx_init")
 
 
 def btx_adamw_step(master: torch.Tensor, m: torch.Tensor, v: torch.Tensor, grad: torch.Tensor, step: int, lr: float,

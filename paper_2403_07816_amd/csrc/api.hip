@@ -85,6 +85,8 @@ bool shapes_ok(int T, int d, int f, int E, int k) {
   return T >= 0 && d > 0 && f > 0 && E >= 1 && E <= kMaxExperts && k >= 1 && k <= E && d % 8 == 0 && f % 8 == 0 &&
          (int64_t)T * k < (int64_t)1 << 31 && (int64_t)T * k * (int64_t)(d > f ? d : f) < (int64_t)1 << 40;
 }
+// valid shapes that the kernels' 32-bit offsets or grid limits cannot take
+bool shapes_supported(int dtype, int T, int d, int f, int E, int k) { return ff_rows_supported(dtype, T * k, d, f, E); }
 
 }  // namespace
 
@@ -158,6 +160,8 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
                     prob_sum, lb_loss, workspace, workspace_bytes, stream);
 }
 
+int btx_init(void) { return ff_prepare(); }
+
 int btx_moe_norm_route(const void* h, int x_dtype, const float* gain, float eps, void* xn, float* rstd,
                        const float* W_router, const float* b_router, const float* U, int T, int d, int E, int k,
                        int route_mode, int lb_mode, float lb_alpha, float tau, float capacity_factor,
@@ -202,6 +206,7 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   if (w13_expert_stride < (int64_t)d * f || w2_expert_stride < (int64_t)d * f) return BTX_ERR_INVALID_ARG;
   if ((save_h1 == nullptr) != (save_h3 == nullptr)) return BTX_ERR_INVALID_ARG;
   if (T == 0) return BTX_OK;
+  if (!shapes_supported(dtype, T, d, f, E, k)) return BTX_ERR_UNSUPPORTED;
   if (!x || !W1 || !W3 || !W2 || !gates || !offsets || !perm || !inv_pos || !out || !workspace)
     return BTX_ERR_INVALID_ARG;
   const FwdWs w = carve_forward(workspace, T, d, f, k, dtype, save_h1 != nullptr);
@@ -247,6 +252,7 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   const int n_dw = (dW1 != nullptr) + (dW3 != nullptr) + (dW2 != nullptr);
   if (n_dw != 0 && n_dw != 3) return BTX_ERR_INVALID_ARG;
   if (T == 0) return BTX_OK;
+  if (!shapes_supported(dtype, T, d, f, E, k)) return BTX_ERR_UNSUPPORTED;
   if (!dY || !x || !W_router || !W1 || !W3 || !W2 || !topk_idx || !gates || !probs || !offsets || !perm || !inv_pos ||
       !gate_sum || !prob_sum || !counts || !save_h1 || !save_h3 || !dX || !dW_router || !workspace)
     return BTX_ERR_INVALID_ARG;

@@ -238,6 +238,10 @@ int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, co
 int launch_bwd_dw2(int dtype, int dW_dtype, const void* ga, const void* dys, const int32_t* offsets, const FfShapes& sh,
                    void* dW2, hipStream_t s);
 size_t ff_scratch_bytes(int dtype, int R, int f);
+// one-time set-up of the expert GEMM kernels on the current device (everything that may not run inside a stream capture)
+int ff_prepare();
+// false when R routed rows are more than the kernels of this dtype and shape can address
+bool ff_rows_supported(int dtype, int R, int d, int f, int E);
 
 struct RouterBwdArgs {
   const void* x; int dtype; const float* W_router; int T, d, E, k, route_mode, lb_mode; float lb_alpha, lb_grad_scale;

@@ -13,6 +13,13 @@ size_t ff_scratch_bytes(int dtype, int R, int f) {
 // The MFMA kernels need d and f to be multiples of 32; other bf16 shapes take the plain path.
 static bool mfma_shape(int d, int f) { return d % 32 == 0 && f % 32 == 0 && d >= 64 && f >= 64; }
 
+int ff_prepare() { return mfma_prepare(); }
+
+bool ff_rows_supported(int dtype, int R, int d, int f, int E) {
+  if (dtype == BTX_BF16 && mfma_shape(d, f)) return mfma_rows_ok(R, E);
+  return generic_rows_ok(R, E);
+}
+
 bool ff_dw_transposed(int dtype, int d, int f) { return dtype == BTX_BF16 && mfma_shape(d, f); }
 int ff_dw_pitch(int R, int E) { return mfma_dw_pitch(R, E); }
 

@@ -3,6 +3,8 @@
 #include "common.h"
 
 namespace btx {
+// the row tiles of the row-grouped products are the y dimension of the launch grid (at most 65535)
+bool generic_rows_ok(int R, int E);
 int generic_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
                       void* h1, void* h3, void* act, hipStream_t s);
 int generic_down(int dtype, const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y,

@@ -207,6 +207,8 @@ struct Generic {
 
 }  // namespace
 
+bool generic_rows_ok(int R, int E) { return ceil_div(R, BT) + E <= 65535; }
+
 int generic_up_swiglu(int dtype, const void* xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
                       void* h1, void* h3, void* act, hipStream_t s) {
   return dtype == BTX_BF16 ? Generic<bf16_t>::up(xs, W1, W3, off, sh, h1, h3, act, s)

@@ -3,6 +3,10 @@
 #include "common.h"
 
 namespace btx {
+// raises the dynamic-LDS limit of every kernel instantiation on the current device (not capturable)
+int mfma_prepare();
+// the weight-gradient products address 255 rows of the transposed, padded operands with 32-bit byte offsets
+bool mfma_rows_ok(int R, int E);
 int mfma_bwd_act_partials(int f);
 // gathered A rows need every byte offset inside the source to fit 32 bits
 bool mfma_gather_ok(int T, int d);

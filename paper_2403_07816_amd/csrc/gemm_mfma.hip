@@ -32,14 +32,13 @@
 #include "gemm_generic.h"
 #include <type_traits>
 
-#ifndef BTX_SUP_M
-#define BTX_SUP_M 16   // default supertile: row tiles x column tiles that run concurrently chip-wide
-#define BTX_SUP_N 16
-#define BTX_XCD_M 4    // XCDs along the supertile's rows (8 / BTX_XCD_M along its columns)
-#endif
-
 namespace btx {
 namespace {
+
+// supertile: row tiles x column tiles that run concurrently chip-wide, and the XCDs along its
+// rows (8 / kXcdM along its columns)
+constexpr int kSupM = 16, kSupN = 16, kXcdM = 4;
+static_assert(kSupM % kXcdM == 0 && 8 % kXcdM == 0 && kSupN % (8 / kXcdM) == 0 && (kSupM * kSupN) % 8 == 0, "supertile");
 
 enum Mode { UP = 0, DOWN = 1, BWD_ACT = 2, BWD_DX = 3, DW13 = 4, DW2 = 5 };
 
@@ -58,7 +57,6 @@ struct MArgs {
   int R;                                // total grouped rows
   int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
   int c_is_f32;
-  int sup_m, sup_n, xcd_m;             // supertile shape in tiles, XCDs along its rows
   int blocks_per_e;                     // grouped-K: block ids per expert (a multiple of 8)
 };
 
@@ -203,7 +201,7 @@ struct Gemm {
     // then the bottom strip column by column) that is cut into 8 equal runs, one per XCD: a
     // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
     // tiles of the row-grouped products depends on the routing and is counted here.
-    const int SM = g.sup_m, SN = g.sup_n, XM = g.xcd_m, XN = 8 / XM;
+    constexpr int SM = kSupM, SN = kSupN, XM = kXcdM, XN = 8 / XM;
     int n_rt = g.tiles_m;
     if (!GROUP_K) {
       n_rt = 0;
@@ -339,8 +337,12 @@ struct Gemm {
 #pragma unroll
       for (int q = 0; q < B_LOADS; ++q) {
         uint32_t off = b_off[q];
-        // grouped-K, strided operand: a k row past the last grouped row is re-pointed at row R-1 (it meets zeros)
-        if (GROUP_K && !B_KC) off = (uint32_t)((min(k0 + b_k[q], g.R - 1) - k0) * g.ldb + b_c[q]) * 2u;
+        // grouped-K, strided operand: a k row past the expert's last grouped row is re-pointed at that last
+        // row.  It meets the zero fill of the transposed operand, so it must hold finite numbers: the
+        // expert's own rows were written by BWD_ACT in this call, whereas the rows behind them belong to
+        // the next expert or, past the last kept row when a capacity limit dropped pairs, to nobody
+        // (workspace bytes nothing has written, possibly NaN patterns).
+        if (GROUP_K && !B_KC) off = (uint32_t)((min(k0 + b_k[q], k_end - 1) - k0) * g.ldb + b_c[q]) * 2u;
         if (is_tail(kt)) {
           if (B_KC) { if (b_hi[q]) off -= 64u; }
           else off = (uint32_t)(min(b_k[q], 31) * g.ldb + b_c[q]) * 2u;
@@ -684,30 +686,36 @@ __global__ __launch_bounds__(WM* WN* kWave) void mfma_gemm_kernel(MArgs g) {
   Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>::run(g, smem);
 }
 
+// The kernels use more dynamic LDS than the default limit allows: the limit is raised once per
+// device and instantiation (idempotent, so a race between threads is harmless).  This must not
+// happen inside a stream capture; mfma_prepare() does it for every instantiation up front.
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
+int raise_lds_limit() {
+  using G = Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
+  static bool attr_set[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BTX_ERR_HIP;
+  if (!attr_set[dev]) {
+    auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            G::LDS_BYTES) != hipSuccess)
+      return BTX_ERR_HIP;
+    attr_set[dev] = true;
+  }
+  return BTX_OK;
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
 int launch(MArgs g, hipStream_t s) {
   using G = Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
   constexpr int BNH = G::DUAL ? BN / 2 : BN;
   g.tiles_n = ceil_div(g.N, BNH);
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
-  if (g.sup_m == 0) { g.sup_m = BTX_SUP_M; g.sup_n = BTX_SUP_N; g.xcd_m = BTX_XCD_M; }
-  if (g.sup_m % g.xcd_m || 8 % g.xcd_m || g.sup_n % (8 / g.xcd_m) || (g.sup_m * g.sup_n) % 8) return BTX_ERR_INVALID_ARG;
   // every tile has exactly one block id below (number of tiles) + 8; see the tile mapping
   g.blocks_per_e = (int)align_up((size_t)g.tiles_m * g.tiles_n, 8) + 8;
   const int total = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
-  auto kern = mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>;
-  // The dynamic LDS limit is raised once per device (idempotent, so a race between threads is
-  // harmless); it must not be set inside a stream capture, so the first call comes before one.
-  static bool attr_set[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BTX_ERR_HIP;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            G::LDS_BYTES) != hipSuccess)
-      return BTX_ERR_HIP;
-    attr_set[dev] = true;
-  }
-  kern<<<total, G::NT, G::LDS_BYTES, s>>>(g);
+  if (int rc = raise_lds_limit<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>()) return rc;
+  mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL><<<total, G::NT, G::LDS_BYTES, s>>>(g);
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }
@@ -719,6 +727,23 @@ bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh
 }  // namespace
 
 constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
+
+int mfma_prepare() {
+  int rc = BTX_OK;
+  auto both = [&](auto mode_tag, auto bn_tag) {
+    constexpr int MODE = decltype(mode_tag)::value, BN = decltype(bn_tag)::value;
+    if (!rc) rc = raise_lds_limit<256, BN, 64, 2, 4, 3, 2, MODE, false>();
+    if constexpr (MODE != DW13 && MODE != DW2)
+      if (!rc) rc = raise_lds_limit<256, BN, 64, 2, 4, 3, 2, MODE, true>();
+  };
+  both(std::integral_constant<int, UP>{}, std::integral_constant<int, 256>{});
+  both(std::integral_constant<int, DOWN>{}, std::integral_constant<int, 256>{});
+  both(std::integral_constant<int, BWD_ACT>{}, std::integral_constant<int, kActBN>{});
+  both(std::integral_constant<int, BWD_DX>{}, std::integral_constant<int, 256>{});
+  both(std::integral_constant<int, DW13>{}, std::integral_constant<int, 256>{});
+  both(std::integral_constant<int, DW2>{}, std::integral_constant<int, 256>{});
+  return rc;
+}
 int mfma_bwd_act_partials(int f) { return ceil_div(f, kActBN); }
 
 bool mfma_gather_ok(int T, int d) { return (int64_t)T * d * 2 < ((int64_t)1 << 32); }
@@ -770,6 +795,7 @@ int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3
 }
 
 int mfma_dw_pitch(int R, int E) { return (int)align_up((size_t)R, 64) + 64 * E; }
+bool mfma_rows_ok(int R, int E) { return ((int64_t)align_up((size_t)R, 64) + 64 * E) * 256 * 2 < ((int64_t)1 << 32); }
 
 int mfma_bwd_dw13(int dW_dtype, const void* xsT, const void* dh1, const void* dh3, const int32_t* off,
                   const FfShapes& sh, void* dW1, void* dW3, hipStream_t s) {

@@ -183,15 +183,16 @@ def test_adamw_rejects_bad_arguments(lib):
     assert step(n=0) == 0
 
 
-def test_probe_rejects_bad_arguments(lib):
-    bad = 1  # BTX_ERR_INVALID_ARG
-    dummy = ctypes.c_void_p(0x1000)
-    assert lib.btx_probe_mfma(None, 1024, dummy, 256, 10, None, None) == bad
-    assert lib.btx_probe_mfma(dummy, 8, dummy, 256, 10, None, None) == bad          # less than one 16-byte chunk
-    assert lib.btx_probe_mfma(ctypes.c_void_p(0x1008), 1024, dummy, 256, 10, None, None) == bad   # misaligned
-    assert lib.btx_probe_mfma(dummy, 1024, dummy, 0, 10, None, None) == bad
-    assert lib.btx_probe_mfma(dummy, 1024, dummy, 256, 0, None, None) == bad
-    assert lib.btx_probe_mfma_out_bytes(256) == 256 * 512 * 4
+def test_shapes_beyond_the_kernels_limits_are_refused_before_any_launch(lib):
+    p, null = ctypes.c_void_p(256), None
+
+    def fwd(T, d, f, E, k, dt):
+        return lib.btx_moe_ff_forward(p, p, p, p, dt, d * f, d * f, T, d, f, E, k, p, p, p, p, null, p, p, p, p,
+                                      1 << 62, null)
+    unsupported = 2
+    assert fwd(8_400_000, 64, 64, 4, 1, 1) == unsupported     # bf16 MFMA path: padded rows * 512 bytes overflow 32 bits
+    assert fwd(4_200_000, 64, 64, 4, 1, 0) == unsupported     # plain path: more row tiles than the grid's y dimension
+    assert fwd(4_200_000, 64, 72, 4, 1, 1) == unsupported     # bf16 with an f the MFMA kernels do not take
 
 
 def test_missing_library_raises(monkeypatch):

@@ -1,11 +1,13 @@
 """Full-size parity: the Llama-2-7B-shaped layer in the launch configuration bench.py
-times (and the other full-size configurations), checked on sampled outputs the oracle
-can compute one by one, plus properties that hold at any size.
+times, and the other full-size configurations.
 
-Sampling: routing, gates, statistics and the grouping are compared for EVERY token
-(the router alone is cheap for the oracle).  Expert outputs, dX rows and dW columns are
-compared on a sample that includes the first and last row of every expert group and rows
-next to the 256-row tile edges."""
+Two passes per configuration.  A fast subset first: routing, gates, statistics and the
+grouping for EVERY token (the router alone is cheap for the oracle), then expert outputs,
+dX rows and dW columns on a sample that includes the first and last row of every expert
+group and rows next to the 256-row tile edges.  Then the complete check: the oracle's
+forward and backward on all tokens (about half a minute of float64 matrix products at the
+benchmark's size) and EVERY element of out, dX, dW1, dW3, dW2, dW_router and db_router
+compared with it."""
 import numpy as np
 import pytest
 import torch
@@ -15,7 +17,7 @@ from paper_2403_07816_amd import binding as B
 from paper_2403_07816_amd import synth
 
 from conftest import assert_close
-from helpers import TOL, check_route, to_np
+from helpers import TOL, check_route, check_router_grads_bf16, to_np
 
 pytestmark = pytest.mark.gpu
 BF16 = torch.bfloat16
@@ -57,8 +59,39 @@ def sample_tokens(fwd, k, n_random, rng):
     return np.array(sorted(toks))
 
 
+def check_complete(x, dY, U, Wr, b, W1, W3, W2, k, mode, alpha, lam, tau, fwd, out, g, what):
+    """Every element of every output against the oracle run on the whole batch.  fwd is the
+    reconciled routing of the batch (check_route): the oracle is forced onto its selection and
+    drop decisions, which differ from its own only on near-tie tokens."""
+    E = W1.shape[0]
+    x_np, Wr_np, b_np = f32(x), f32(Wr), (None if b is None else f32(b))
+    W1n = [f32(W1[e]) for e in range(E)]
+    W3n = [f32(W3[e]) for e in range(E)]
+    W2n = [f32(W2[e]) for e in range(E)]
+    U_np = None if U is None else f32(U)
+    full = O.moe_forward(x_np, Wr_np, b_np, W1n, W3n, W2n, k, mode, U_np, alpha, O.LB_TOKEN_FRAC, forced_idx=fwd["idx"],
+                         tau=tau, forced_dropped=fwd["dropped"])
+    assert np.array_equal(full["idx"], fwd["idx"])
+    assert_close(f32(out), full["out"], TOL[BF16], f"{what}: out (every element)")
+    if g is None:
+        return None
+    dY_np = f32(dY)
+    ref = O.moe_backward(x_np, Wr_np, b_np, W1n, W3n, W2n, k, mode, dY_np, full, alpha, O.LB_TOKEN_FRAC, lam, tau=tau)
+    assert_close(f32(g.dX), ref["dX"], TOL[BF16], f"{what}: dX (every element)")
+    for name in ("dW1", "dW3", "dW2"):
+        for e in range(E):
+            got = f32(getattr(g, name)[e])
+            if ref[name][e] is None or fwd["offsets"][e + 1] == fwd["offsets"][e]:
+                assert not got.any(), f"{what}: {name}[{e}] must be zero for an expert without rows"
+            else:
+                assert_close(got, ref[name][e], TOL[BF16], f"{what}: {name}[{e}] (every element)")
+                ref[name][e] = None          # free the float64 copy
+    L = {"x": x, "dY": dY, "W1": W1, "W3": W3, "W2": W2}
+    return check_router_grads_bf16(g, L, full, ref, mode, tau, what=what)
+
+
 def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True, n_random=24, n_cols=6, seed=0,
-             noise=None, tau=1.0, cf=0.0):
+             noise=None, tau=1.0, cf=0.0, complete=True, what=""):
     rng = np.random.default_rng(seed)
     E, d, f = W1.shape[0], W1.shape[1], W1.shape[2]
     x, dY = L["x"][:T].contiguous(), L["dY"][:T].contiguous()
@@ -79,6 +112,8 @@ def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True
                         forced_idx=forced, tau=tau, forced_dropped=fwd["dropped"][toks])
     assert_close(f32(out[toks]), sub["out"], TOL[BF16], "out[sample]")
     if not backward:
+        if complete:
+            check_complete(x, None, U, Wr, b, W1, W3, W2, k, mode, alpha, lam, tau, fwd, out, None, what)
         return r, out, None, fwd
 
     g = B.btx_moe_ff_backward(dY, x, Wr, W1, W3, W2, r, h1, h3, mode, B.BTX_LB_TOKEN_FRAC, alpha, lam,
@@ -106,6 +141,8 @@ def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True
     scale = np.abs(dWr).sum(axis=1).max()
     assert np.abs(dWr.sum(axis=1)).max() <= 1e-4 * scale
     assert abs(f32(g.db_router).astype(np.float64).sum()) <= 1e-4 * np.abs(f32(g.db_router)).sum()
+    if complete:
+        check_complete(x, dY, U, Wr, b, W1, W3, W2, k, mode, alpha, lam, tau, fwd, out, g, what)
     return r, out, g, fwd
 
 
@@ -137,12 +174,12 @@ def test_config2_block_rmsnorm_route_and_norm_backward_every_row(big):
 
 def test_config1_forward_T4096(big):
     run_full(big, 4096, 2, B.BTX_ROUTE_TOPK_RENORM, 0.0, 0.0, big["W1"], big["W3"], big["W2"], big["W_router"],
-             backward=False)
+             backward=False, what="C1 T=4096 forward")
 
 
 def test_config2_forward_backward_T16384_as_benchmarked(big):
     r, out, g, fwd = run_full(big, T_FULL, 2, B.BTX_ROUTE_TOPK_RENORM, 0.01, 1.0, big["W1"], big["W3"], big["W2"],
-                              big["W_router"])
+                              big["W_router"], what="C2 T=16384 top-2")
     # run-to-run determinism at full size (no atomics anywhere)
     x, dY = big["x"], big["dY"]
     r2 = B.btx_moe_route(x, big["W_router"], None, None, 2, lb_alpha=0.01)
@@ -160,14 +197,14 @@ def test_config3_gumbel_sample_top1(big):
     u = torch.rand((T_FULL, 4), generator=g, device="cuda", dtype=torch.float32).clamp_(1e-7, 1 - 1e-7)
     noise = -torch.log(-torch.log(u))
     run_full(big, T_FULL, 1, B.BTX_ROUTE_GUMBEL_TOP1, 0.01, 1.0, big["W1"], big["W3"], big["W2"], big["W_router"],
-             noise=noise, tau=0.5)
+             noise=noise, tau=0.5, what="C3 Gumbel sample top-1")
 
 
 def test_config3_switch_with_capacity_factor(big):
     """Switch routing at the capacity factor of Sec. 4.3 (1.5) with a router that overloads expert 0:
     it keeps ceil(1.5 * T / 4) = 6144 tokens and the rest of its tokens pass through with no FF output."""
     r, out, g, fwd = run_full(big, T_FULL, 1, B.BTX_ROUTE_SWITCH_TOP1, 0.01, 1.0, big["W1"], big["W3"], big["W2"],
-                              big["W_router"], bias=[2.0, 0.0, 0.0, 0.0], cf=1.5)
+                              big["W_router"], bias=[2.0, 0.0, 0.0, 0.0], cf=1.5, what="C3 Switch cf=1.5")
     assert int(r.offsets[1]) == 6144 and fwd["counts"][0] > 6144
     dropped = (r.inv_pos[:, 0] < 0)
     assert int(dropped.sum()) == fwd["counts"][0] - 6144
@@ -177,7 +214,7 @@ def test_config3_switch_with_capacity_factor(big):
 @pytest.mark.parametrize("mode", [B.BTX_ROUTE_SWITCH_TOP1, B.BTX_ROUTE_SAMPLE_TOP1])
 def test_config3_top1_variants_imbalanced(big, mode):
     r, out, g, fwd = run_full(big, T_FULL, 1, mode, 0.01, 1.0, big["W1"], big["W3"], big["W2"], big["W_router"],
-                              bias=[2.0, 0.0, 0.0, 0.0])
+                              bias=[2.0, 0.0, 0.0, 0.0], what=f"C3 top-1 mode {mode}, bias +2")
     share = fwd["counts"][0] / T_FULL
     # bias +2 on logits of std ~1.28: ~0.6 of the softmax mass, ~0.7 of the argmaxes
     assert 0.5 < share < 0.8, f"expert 0 should receive the bulk of the tokens, got {share:.2f}"
@@ -191,7 +228,8 @@ def test_config4_fine_grained_experts_E32_top8(big):
         assert np.array_equal(f32(W1[c]), o1[c]) and np.array_equal(f32(W3[c]), o3[c])
         assert np.array_equal(f32(W2[c]), o2[c])
     Wr = synth.make_layer(8, D, 8, 1, device="cuda", router_E=32)["W_router"]
-    run_full(big, T_FULL, 8, B.BTX_ROUTE_TOPK_RENORM, 0.01, 1.0, W1, W3, W2, Wr, n_random=8, n_cols=2)
+    run_full(big, T_FULL, 8, B.BTX_ROUTE_TOPK_RENORM, 0.01, 1.0, W1, W3, W2, Wr, n_random=8, n_cols=2,
+             what="C4 E=32 f=1376 top-8")
 
 
 def test_config4_merge_average_7b_non_ff_parameter_set():
