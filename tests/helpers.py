@@ -156,41 +156,46 @@ def router_grads_from_dg(x, dg, fwd, ref, mode, tau=1.0):
     return x.T @ ds, ds.sum(axis=0)
 
 
+MODEL_TOL = 2e-3     # the library's router gradients against the bf16 storage model (observed: at most 5e-4)
+
+
 def check_router_grads_bf16(g, L, fwd, ref, mode, tau=1.0, what=""):
-    """The bf16 bar for dW_router / db_router, and the evidence for it.  Returns the measured numbers.
-      * the stated bar 2e-2 times max(1, kappa), kappa = the oracle-computed amplification of a relative
-        error in dg by the cancellation inside the gate Jacobian (router_condition);
-      * the library's error may not exceed what rounding the saved h1, h3 to bf16 costs by itself
-        (bf16_storage_model_dg) by more than half, plus the plain fp32-level slack: a kernel that lost
-        accuracy of its own would fail this whatever kappa is."""
+    """dW_router / db_router of the bf16 path.  Returns the measured numbers.
+
+    d(logits) of top-k routing is g_j (dg_j - sum_i g_i dg_i): for experts that drifted little from
+    one seed the dg_j nearly cancel, and the 2^-9 roundings of the saved up-projections h1, h3 (which
+    are independent between experts) do not.  Two assertions:
+      * against bf16_storage_model_dg, i.e. the exact gradient of a layer whose h1, h3 were rounded
+        to bf16 and nothing else: within MODEL_TOL.  Whatever the library's own arithmetic adds to
+        the unavoidable storage error is bounded by this, a tenth of the bar;
+      * against the exact oracle: the stated 2e-2, except where the storage model itself is further
+        than that from the oracle (db_router on a few hundred tokens): there the model's own error
+        plus a tenth.
+    kappa, the worst-case amplification of a relative error in dg by that cancellation
+    (router_condition), is reported for orientation only."""
     from conftest import rel_err
     tol = TOL[torch.bfloat16]
     kappa = router_condition(fwd, ref, mode)
     dg_model = bf16_storage_model_dg(to_np(L["x"]), to_np(L["dY"]), experts_np(L["W1"]), experts_np(L["W3"]),
                                      experts_np(L["W2"]), fwd)
     dWr_m, db_m = router_grads_from_dg(to_np(L["x"]), dg_model, fwd, ref, mode, tau)
-    got_w, got_b = to_np(g.dW_router), to_np(g.db_router)
-    res = {"kappa": kappa, "dW_router": rel_err(got_w, ref["dW_router"]), "db_router": rel_err(got_b, ref["db_router"]),
-           "dW_router_storage_model": rel_err(dWr_m, ref["dW_router"]),
-           "db_router_storage_model": rel_err(db_m, ref["db_router"]),
-           "dg": rel_err(dg_model, ref["dg"]), "dW_router_vs_model": rel_err(got_w, dWr_m),
-           "db_router_vs_model": rel_err(got_b, db_m)}
-    print(f"[router grads {what}] kappa={kappa:.2f} "
-          f"dW_router gpu fro/max={res['dW_router'][0]:.3e}/{res['dW_router'][1]:.3e} "
-          f"storage-model={res['dW_router_storage_model'][0]:.3e}/{res['dW_router_storage_model'][1]:.3e}  "
-          f"db_router gpu={res['db_router'][0]:.3e}/{res['db_router'][1]:.3e} "
-          f"storage-model={res['db_router_storage_model'][0]:.3e}/{res['db_router_storage_model'][1]:.3e}  "
-          f"dg storage-model fro={res['dg'][0]:.3e}  gpu vs storage-model: dW_router {res['dW_router_vs_model'][0]:.3e}/"
-          f"{res['dW_router_vs_model'][1]:.3e} db_router {res['db_router_vs_model'][0]:.3e}/{res['db_router_vs_model'][1]:.3e}",
-          flush=True)
-    rtol = tol * max(1.0, kappa)
-    assert_close(got_w, ref["dW_router"], rtol, "dW_router")
-    assert_close(got_b, ref["db_router"], rtol, "db_router")
+    got = {"dW_router": to_np(g.dW_router), "db_router": to_np(g.db_router)}
+    model = {"dW_router": dWr_m, "db_router": db_m}
+    res = {"kappa": kappa, "dg_storage_model": rel_err(dg_model, ref["dg"])}
     for name in ("dW_router", "db_router"):
+        res[name] = rel_err(got[name], ref[name])
+        res[name + "_storage_model"] = rel_err(model[name], ref[name])
+        res[name + "_vs_model"] = rel_err(got[name], model[name])
+    print(f"[router grads {what}] kappa={kappa:.2f} dg storage-model fro={res['dg_storage_model'][0]:.3e} | " +
+          " | ".join(f"{n}: vs oracle {res[n][0]:.3e}/{res[n][1]:.3e}, storage model vs oracle "
+                     f"{res[n + '_storage_model'][0]:.3e}/{res[n + '_storage_model'][1]:.3e}, vs storage model "
+                     f"{res[n + '_vs_model'][0]:.3e}/{res[n + '_vs_model'][1]:.3e}" for n in ("dW_router", "db_router")),
+          flush=True)
+    for name in ("dW_router", "db_router"):
+        assert_close(got[name], model[name], MODEL_TOL, f"{name} against the bf16 storage model")
         for i, kind in enumerate(("fro", "max")):
-            allowed = 1.5 * res[name + "_storage_model"][i] + 2e-3
-            assert res[name][i] <= max(tol, allowed), \
-                f"{name} {kind} error {res[name][i]:.3e} exceeds what bf16 storage of h1/h3 explains ({allowed:.3e})"
+            bar = max(tol, 1.1 * res[name + "_storage_model"][i])
+            assert res[name][i] <= bar, f"{name}: {kind} error {res[name][i]:.3e} against the oracle exceeds {bar:.3e}"
     return res
 
 
