@@ -84,7 +84,8 @@ int btx_version(void);
  * kernel (they use all 160 KB of a compute unit's LDS).  Optional: the first bf16 call of
  * btx_moe_ff_forward / btx_moe_ff_backward on a device does the same by itself, but that
  * set-up cannot be recorded into a HIP graph, so a caller that captures its very first step
- * calls btx_init() before beginning the capture (once per device that it uses).
+ * calls btx_init() before beginning the capture (once per device that it uses).  It also
+ * looks up the device address of btx_moe_route_noalloc's fixed workspace.
  * Idempotent.  Errors: BTX_ERR_HIP. */
 int btx_init(void);
 
@@ -152,6 +153,29 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
                   float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts, int32_t* offsets,
                   int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum, float* lb_loss,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * btx_moe_route_noalloc - btx_moe_route for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results, but without the workspace pair: the
+ * workspace is a fixed array of btx_moe_route_noalloc_max_workspace_bytes() (4 MiB) inside the
+ * library's device image, which every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing.
+ *   - A problem whose btx_moe_route_workspace_bytes(T,d,E,k) exceeds that size is refused with
+ *     BTX_ERR_WORKSPACE before anything else is checked or launched (T = 16384, d = 4096,
+ *     E = 64 needs 2 MiB).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race and give unspecified results; calls on one stream are safe.
+ *     Nothing in the array has to start at zero, every call overwrites what it reads.
+ *   - The array's device address is looked up on the first call on a device (or by btx_init);
+ *     that look-up is not a stream operation and may precede a capture.
+ */
+size_t btx_moe_route_noalloc_max_workspace_bytes(void);
+int btx_moe_route_noalloc(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U,
+                          int T, int d, int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau,
+                          float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts,
+                          int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum,
+                          float* lb_loss, void* stream);
 
 /* ---------------------------------------------------------------------------
  * btx_moe_norm_route - btx_moe_route with the block's pre-normalisation folded into the

@@ -32,6 +32,8 @@ _SIGNATURES = {
     "btx_init": (_i, []),
     "btx_moe_route_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "btx_moe_route": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp, _sz, _vp]),
+    "btx_moe_route_noalloc_max_workspace_bytes": (_sz, []),
+    "btx_moe_route_noalloc": (_i, [_vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 + [_vp]),
     "btx_moe_norm_route": (_i, [_vp, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _f, _f] + [_vp] * 10 +
                            [_vp, _sz, _vp]),
     "btx_rmsnorm_backward_workspace_bytes": (_sz, [_i, _i]),
@@ -137,6 +139,24 @@ def btx_moe_route(x: torch.Tensor, W_router: torch.Tensor, b_router: Optional[to
                            _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos), _ptr(r.gate_sum), _ptr(r.prob_sum),
                            _ptr(r.lb_loss), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_route")
+    return r
+
+
+def btx_moe_route_noalloc(x: torch.Tensor, W_router: torch.Tensor, out: Routing, b_router: Optional[torch.Tensor] = None,
+                          U: Optional[torch.Tensor] = None, k: int = 2, route_mode: int = BTX_ROUTE_TOPK_RENORM,
+                          lb_mode: int = BTX_LB_TOKEN_FRAC, lb_alpha: float = 0.0, tau: float = 1.0,
+                          capacity_factor: float = 0.0) -> Routing:
+    """btx_moe_route into caller-allocated outputs, with the library's fixed workspace: allocates nothing."""
+    lib = load_library()
+    T, d = x.shape
+    E = W_router.shape[1]
+    assert W_router.shape[0] == d and W_router.dtype == torch.float32
+    r = out
+    st = lib.btx_moe_route_noalloc(_ptr(x), _dtype_code(x), _ptr(W_router), _ptr(b_router), _ptr(U), T, d, E, k,
+                                   route_mode, lb_mode, lb_alpha, tau, capacity_factor, _ptr(r.topk_idx), _ptr(r.gates),
+                                   _ptr(r.probs), _ptr(r.counts), _ptr(r.offsets), _ptr(r.perm), _ptr(r.inv_pos),
+                                   _ptr(r.gate_sum), _ptr(r.prob_sum), _ptr(r.lb_loss), _stream())
+    _check(st, "btx_moe_route_noalloc")
     return r
 
 

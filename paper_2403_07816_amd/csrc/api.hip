@@ -81,6 +81,26 @@ struct StageTimer {
     if (int rc_ = (call)) return rc_;  \
   } while (0)
 
+// Workspace of btx_moe_route_noalloc: a fixed array in the library's device image instead of a
+// buffer the caller allocates.  Every GPU holds its own copy at its own address; the array's
+// name is only a host-side handle, so the address is looked up once per device (with that
+// device current) and the kernels are given that pointer.
+constexpr size_t kStaticRouteBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticRouteBytes];
+void* g_scratch_ptr[64] = {};
+
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BTX_ERR_HIP;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BTX_ERR_HIP;
+    g_scratch_ptr[dev] = p;       // threads racing here store the same value
+  }
+  *out = g_scratch_ptr[dev];
+  return BTX_OK;
+}
+
 bool shapes_ok(int T, int d, int f, int E, int k) {
   return T >= 0 && d > 0 && f > 0 && E >= 1 && E <= kMaxExperts && k >= 1 && k <= E && d % 8 == 0 && f % 8 == 0 &&
          (int64_t)T * k < (int64_t)1 << 31 && (int64_t)T * k * (int64_t)(d > f ? d : f) < (int64_t)1 << 40;
@@ -160,7 +180,32 @@ int btx_moe_route(const void* x, int x_dtype, const float* W_router, const float
                     prob_sum, lb_loss, workspace, workspace_bytes, stream);
 }
 
-int btx_init(void) { return ff_prepare(); }
+int btx_init(void) {
+  void* p = nullptr;
+  if (int rc = static_scratch(&p)) return rc;   // also looks up this device's copy of the fixed workspace
+  return ff_prepare();
+}
+
+size_t btx_moe_route_noalloc_max_workspace_bytes(void) { return kStaticRouteBytes; }
+
+int btx_moe_route_noalloc(const void* x, int x_dtype, const float* W_router, const float* b_router, const float* U, int T,
+                          int d, int E, int k, int route_mode, int lb_mode, float lb_alpha, float tau,
+                          float capacity_factor, int32_t* topk_idx, float* gates, float* probs, int32_t* counts,
+                          int32_t* offsets, int32_t* perm, int32_t* inv_pos, float* gate_sum, float* prob_sum,
+                          float* lb_loss, void* stream) {
+  // the size check comes first: a problem that does not fit is refused whatever else is wrong with it
+  if (T > 0 && d > 0 && E >= 1 && E <= kMaxExperts && k >= 1 && k <= E &&
+      route_workspace_bytes(T, d, E, k) > kStaticRouteBytes)
+    return BTX_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (T > 0) {
+    if (int rc = static_scratch(&ws)) return rc;
+  }
+  return route_impl(x, x_dtype, nullptr, 0.f, nullptr, nullptr, W_router, b_router, U, T, d, E, k, route_mode, lb_mode,
+                    lb_alpha, tau, capacity_factor, topk_idx, gates, probs, counts, offsets, perm, inv_pos, gate_sum,
+                    prob_sum, lb_loss, ws, kStaticRouteBytes, stream);
+}
+
 
 int btx_moe_norm_route(const void* h, int x_dtype, const float* gain, float eps, void* xn, float* rstd,
                        const float* W_router, const float* b_router, const float* U, int T, int d, int E, int k,
