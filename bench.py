@@ -431,6 +431,7 @@ def main():
     ap.add_argument("--variant", default="top2", choices=sorted(VARIANTS),
                     help="configuration to time as the headline; only top2 is the benchmark of record")
     ap.add_argument("--no-configs", action="store_true", help="skip the other named configurations and the merge")
+    ap.add_argument("--merge-only", action="store_true", help="only the parameter averaging (profiling runs)")
     ap.add_argument("--no-selfcheck", action="store_true", help="skip the parity and determinism checks (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -440,6 +441,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B.btx_init()
+    if args.merge_only:
+        print(json.dumps(merge_bench(dev)))
+        return
     V = VARIANTS[args.variant]
     T = args.tokens or V["T"]
     main_layer = Layer(V, T, dev)

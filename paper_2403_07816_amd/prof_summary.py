@@ -2,7 +2,12 @@
 summaries kept under profiles/.
 
   python -m paper_2403_07816_amd.prof_summary stats  <bench_kernel_stats.csv>
-  python -m paper_2403_07816_amd.prof_summary pmc    <pmc_counter_collection.csv> [...]
+  python -m paper_2403_07816_amd.prof_summary pmc    [--calib KERNEL:READ_KIB:WRITE_KIB] <pmc_counter_collection.csv> [...]
+
+--calib names a plain streaming kernel of the same run whose traffic is known (KiB read and written per
+dispatch): FETCH_SIZE and WRITE_SIZE of every kernel are to be divided by what those counters read per
+KiB that kernel moved.  The factors and a digest of the GEMM kernel source go into "#" lines that
+bench.py parses.
 """
 from __future__ import annotations
 
@@ -31,7 +36,14 @@ def stats(path: str) -> None:
               f"{float(r['MinNs']) / 1e3:10.1f} {float(r['MaxNs']) / 1e3:10.1f} {float(r['Percentage']):7.2f}")
 
 
-def pmc(paths) -> None:
+def source_digest() -> str:
+    import hashlib
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "gemm_mfma.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+
+
+def pmc(paths, calib=None) -> None:
     agg = collections.OrderedDict()
     dur = collections.OrderedDict()     # kernel -> counter -> durations (ns) of the dispatches it was read on
     for path in paths:
@@ -43,6 +55,19 @@ def pmc(paths) -> None:
                 float(r["Counter_Value"]))
             dur.setdefault(k, {}).setdefault(r["Counter_Name"], []).append(
                 float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+    print(f"# gemm_mfma.hip sha256/16: {source_digest()}")
+    if calib:
+        kname, read_kib, write_kib = calib.split(":")
+        match = [k for k in agg if k.startswith(kname)]
+        if match:
+            c = agg[match[0]]
+            parts = []
+            if "FETCH_SIZE" in c:
+                parts.append(f"FETCH_SIZE={sum(c['FETCH_SIZE']) / len(c['FETCH_SIZE']) / float(read_kib):.4f}")
+            if "WRITE_SIZE" in c:
+                parts.append(f"WRITE_SIZE={sum(c['WRITE_SIZE']) / len(c['WRITE_SIZE']) / float(write_kib):.4f}")
+            print(f"# calibration: {' '.join(parts)}   (counter KiB per KiB that {match[0]} is known to move: "
+                  f"{read_kib} KiB read, {write_kib} KiB written per dispatch)")
     for name, counters in agg.items():
         print(name)
         for c, v in counters.items():
@@ -62,4 +87,10 @@ def pmc(paths) -> None:
 if __name__ == "__main__":
     if len(sys.argv) < 3 or sys.argv[1] not in ("stats", "pmc"):
         sys.exit(__doc__)
-    stats(sys.argv[2]) if sys.argv[1] == "stats" else pmc(sys.argv[2:])
+    if sys.argv[1] == "stats":
+        stats(sys.argv[2])
+    else:
+        rest, calib = sys.argv[2:], None
+        if rest[0] == "--calib":
+            calib, rest = rest[1], rest[2:]
+        pmc(rest, calib)
