@@ -143,6 +143,20 @@ __device__ __forceinline__ float wave_max(float v) {
   return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (all lanes active): four DPP shifts inside
+// each row of 16 lanes, then the row totals (lanes 15, 31, 47) are added to the rows behind them.
+constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;   // row_shr:n, zeros shifted in
+__device__ __forceinline__ int wave_incl_scan_i32(int v, int lane) {
+  v += dpp_i32<kDppShr1>(v);
+  v += dpp_i32<kDppShr2>(v);
+  v += dpp_i32<kDppShr4>(v);
+  v += dpp_i32<kDppShr8>(v);
+  const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+            t2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane >> 4;
+  return v + (row == 0 ? 0 : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2);
+}
+
 // Which expert owns grouped row-tile `tile` when every expert's rows are cut
 // into tiles of BM rows, experts laid one after another.  Returns false past
 // the last tile.  offsets has E+1 entries.

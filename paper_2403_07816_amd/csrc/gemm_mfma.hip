@@ -202,11 +202,16 @@ struct Gemm {
     // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
     // tiles of the row-grouped products depends on the routing and is counted here.
     constexpr int SM = kSupM, SN = kSupN, XM = kXcdM, XN = 8 / XM;
-    int n_rt = g.tiles_m;
-    if (!GROUP_K) {
-      n_rt = 0;
-      for (int x = 0; x < g.E; ++x) n_rt += (g.offsets[x + 1] - g.offsets[x] + BM - 1) / BM;
-    }
+    // The experts' row ranges are looked at by the whole wavefront at once, lane x taking expert x (at
+    // most 64): one load and two prefix sums instead of loops of dependent scalar loads over the
+    // experts, which with 32 experts took longer than a tenth of a short tile's main loop.
+    const int xe = min(lane, g.E - 1);
+    const int x_o0 = g.offsets[xe], x_o1 = g.offsets[xe + 1];
+    const int x_n = lane < g.E ? x_o1 - x_o0 : 0;
+    const int x_nt = (x_n + BM - 1) / BM, x_pad = (x_n + 63) & ~63;
+    const int x_nt_incl = GROUP_K ? 0 : wave_incl_scan_i32(x_nt, lane);       // row tiles up to and including expert x
+    const int x_pad_incl = (GROUP_K || MODE == BWD_ACT) ? wave_incl_scan_i32(x_pad, lane) : 0;   // padded rows likewise
+    const int n_rt = GROUP_K ? g.tiles_m : __builtin_amdgcn_readlane(x_nt_incl, kWave - 1);
     const int fr = n_rt / SM, fc = g.tiles_n / SN;     // whole supertile rows / columns
     const int blocks_full = fr * fc * SM * SN;
     int id = blockIdx.x;
@@ -242,16 +247,21 @@ struct Gemm {
     if (GROUP_K) {
       row0 = tile_m * BM;
       row_end = g.M;
-      k_begin = g.offsets[e];
-      k_end = g.offsets[e + 1];
-      for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
+      k_begin = __builtin_amdgcn_readlane(x_o0, e);
+      k_end = __builtin_amdgcn_readlane(x_o1, e);
     } else {
-      if (!find_row_tile(g.offsets, g.E, BM, tile_m, e, row0, row_end)) return;
+      // the expert whose row tiles include tile_m: the first lane whose running total exceeds it
+      const unsigned long long owners = __ballot(x_nt_incl > tile_m);
+      if (owners == 0) return;                          // past the last row tile of this routing
+      e = __ffsll((long long)owners) - 1;
+      const int t = tile_m - (__builtin_amdgcn_readlane(x_nt_incl, e) - __builtin_amdgcn_readlane(x_nt, e));
+      row0 = __builtin_amdgcn_readlane(x_o0, e) + t * BM;
+      row_end = __builtin_amdgcn_readlane(x_o1, e);
       k_begin = 0;
       k_end = g.K;
-      if (MODE == BWD_ACT && g.T2)                      // where expert e starts in the transposed outputs
-        for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
     }
+    if (GROUP_K || MODE == BWD_ACT)                     // where expert e starts in the transposed, padded operands
+      kp_begin = __builtin_amdgcn_readlane(x_pad_incl, e) - __builtin_amdgcn_readlane(x_pad, e);
     const int col0 = tile_n * BNH;
 
     const bf16_t* Bp0 = g.B0;
@@ -557,7 +567,7 @@ struct Gemm {
           // scattered 16-byte stores cost the address unit four times as much.  Rows past the
           // group's end are zeros (see the gate above) and are written up to the 64-row padding.
           typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-          const int o_e = g.offsets[e];
+          const int o_e = __builtin_amdgcn_readlane(x_o0, e);
           const int pad_e = (row_end - o_e + 63) & ~63;
           const int fr = 8 * lane_c + (lane_m >> 2), fa4 = lane_m & 3;
           const int qc = lane >> 2, qg = lane & 3;        // read-back view: column within 16, 8-row chunk
