@@ -202,16 +202,23 @@ struct Gemm {
     // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
     // tiles of the row-grouped products depends on the routing and is counted here.
     constexpr int SM = kSupM, SN = kSupN, XM = kXcdM, XN = 8 / XM;
-    // The experts' row ranges are looked at by the whole wavefront at once, lane x taking expert x (at
-    // most 64): one load and two prefix sums instead of loops of dependent scalar loads over the
-    // experts, which with 32 experts took longer than a tenth of a short tile's main loop.
-    const int xe = min(lane, g.E - 1);
-    const int x_o0 = g.offsets[xe], x_o1 = g.offsets[xe + 1];
-    const int x_n = lane < g.E ? x_o1 - x_o0 : 0;
-    const int x_nt = (x_n + BM - 1) / BM, x_pad = (x_n + 63) & ~63;
-    const int x_nt_incl = GROUP_K ? 0 : wave_incl_scan_i32(x_nt, lane);       // row tiles up to and including expert x
-    const int x_pad_incl = (GROUP_K || MODE == BWD_ACT) ? wave_incl_scan_i32(x_pad, lane) : 0;   // padded rows likewise
-    const int n_rt = GROUP_K ? g.tiles_m : __builtin_amdgcn_readlane(x_nt_incl, kWave - 1);
+    // Row-grouped products: the experts' row ranges are looked at by the whole wavefront at once, lane x
+    // taking expert x (at most 64): one load and two prefix sums instead of loops of dependent scalar
+    // loads over the experts, which with 32 experts took longer than a tenth of a short tile's main loop.
+    // (The products grouped along K know their expert from the block id and keep the one short loop.)
+    int x_o0 = 0, x_o1 = 0, x_nt = 0, x_pad = 0, x_nt_incl = 0, x_pad_incl = 0;
+    int n_rt = g.tiles_m;
+    if (!GROUP_K) {
+      const int xe = min(lane, g.E - 1);
+      x_o0 = g.offsets[xe];
+      x_o1 = g.offsets[xe + 1];
+      const int x_n = lane < g.E ? x_o1 - x_o0 : 0;
+      x_nt = (x_n + BM - 1) / BM;
+      x_pad = (x_n + 63) & ~63;
+      x_nt_incl = wave_incl_scan_i32(x_nt, lane);                              // row tiles up to and including expert x
+      if (MODE == BWD_ACT) x_pad_incl = wave_incl_scan_i32(x_pad, lane);       // padded rows likewise
+      n_rt = __builtin_amdgcn_readlane(x_nt_incl, kWave - 1);
+    }
     const int fr = n_rt / SM, fc = g.tiles_n / SN;     // whole supertile rows / columns
     const int blocks_full = fr * fc * SM * SN;
     int id = blockIdx.x;
@@ -247,8 +254,9 @@ struct Gemm {
     if (GROUP_K) {
       row0 = tile_m * BM;
       row_end = g.M;
-      k_begin = __builtin_amdgcn_readlane(x_o0, e);
-      k_end = __builtin_amdgcn_readlane(x_o1, e);
+      k_begin = g.offsets[e];
+      k_end = g.offsets[e + 1];
+      for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
     } else {
       // the expert whose row tiles include tile_m: the first lane whose running total exceeds it
       const unsigned long long owners = __ballot(x_nt_incl > tile_m);
@@ -260,7 +268,7 @@ struct Gemm {
       k_begin = 0;
       k_end = g.K;
     }
-    if (GROUP_K || MODE == BWD_ACT)                     // where expert e starts in the transposed, padded operands
+    if (MODE == BWD_ACT)                                // where expert e starts in the transposed, padded output
       kp_begin = __builtin_amdgcn_readlane(x_pad_incl, e) - __builtin_amdgcn_readlane(x_pad, e);
     const int col0 = tile_n * BNH;
 

@@ -10,6 +10,8 @@
 //                ascending j in fp32, one rounding.  No atomics: every output row has
 //                exactly one writer.
 // Rows are moved as 16-byte chunks, consecutive lanes on consecutive chunks.
+#include <type_traits>
+
 #include "common.h"
 
 namespace btx {
@@ -99,7 +101,9 @@ template <> struct Chunk<float> {
   }
 };
 
-template <typename ET>
+// KMAX: slots whose grouped rows and gates a wavefront keeps in registers; the rows of those slots are
+// requested together for every 16-byte column chunk (k > KMAX: the remaining slots are looked up as they come).
+template <typename ET, int KMAX>
 __global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restrict__ y, const float* __restrict__ gates,
                                                            const int32_t* __restrict__ inv_pos,
                                                            const u32x4* __restrict__ residual, u32x4* __restrict__ out,
@@ -108,12 +112,31 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const u32x4* __restri
   const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
   const int t = blockIdx.x * (kThreads / kWave) + wave;
   if (t >= T) return;
+  int row[KMAX];
+  float gate[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    row[j] = j < k ? inv_pos[(size_t)t * k + j] : -1;             // -1: no such slot, or the pair was dropped
+    gate[j] = (j < k && gates) ? gates[(size_t)t * k + j] : 1.f;
+  }
   for (int c = lane; c < chunks_per_row; c += kWave) {
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    u32x4 w[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) w[j] = y[(size_t)max(row[j], 0) * chunks_per_row + c];   // all slots in flight
     if (residual) Chunk<ET>::unpack(residual[(size_t)t * chunks_per_row + c], acc);   // block input, added in fp32
-    for (int j = 0; j < k; ++j) {
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {          // ascending slot order, as the definition sums
+      float v[N];
+      Chunk<ET>::unpack(w[j], v);
+      if (row[j] >= 0) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fmaf(gate[j], v[i], acc[i]);
+      }
+    }
+    for (int j = KMAX; j < k; ++j) {
       const int r = inv_pos[(size_t)t * k + j];
       if (r < 0) continue;                  // pair dropped at its expert's capacity
       const float g = gates ? gates[(size_t)t * k + j] : 1.f;
@@ -152,14 +175,19 @@ int launch_combine(const void* y, const float* gates, const int32_t* inv_pos, co
   const int esz = dtype == BTX_BF16 ? 2 : 4;
   const int chunks = d * esz / 16;
   dim3 grid(ceil_div(T, kThreads / kWave));
-  if (dtype == BTX_BF16)
-    combine_kernel<bf16_t><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
-                                                     static_cast<const u32x4*>(residual), static_cast<u32x4*>(out), T,
-                                                     k, chunks);
-  else
-    combine_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<const u32x4*>(y), gates, inv_pos,
-                                                    static_cast<const u32x4*>(residual), static_cast<u32x4*>(out), T,
-                                                    k, chunks);
+  auto run = [&](auto tag, auto kmax) {
+    using ET = decltype(tag);
+    combine_kernel<ET, decltype(kmax)::value><<<grid, kThreads, 0, s>>>(
+        static_cast<const u32x4*>(y), gates, inv_pos, static_cast<const u32x4*>(residual), static_cast<u32x4*>(out), T, k,
+        chunks);
+  };
+  auto by_k = [&](auto tag) {
+    if (k <= 1) run(tag, std::integral_constant<int, 1>{});
+    else if (k <= 2) run(tag, std::integral_constant<int, 2>{});
+    else run(tag, std::integral_constant<int, 4>{});   // eight slots in flight were no faster than four
+  };
+  if (dtype == BTX_BF16) by_k(bf16_t{});
+  else by_k(float{});
   BTX_LAUNCH_CHECK();
   return BTX_OK;
 }

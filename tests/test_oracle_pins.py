@@ -394,6 +394,7 @@ def test_backward_with_dropped_pairs_matches_finite_differences(mode, k, cf):
     np.testing.assert_allclose(g["db_router"], fd(b), rtol=2e-6, atol=2e-8)
     for e in range(E):
         np.testing.assert_allclose(g["dW1"][e], fd(W1[e]), rtol=2e-6, atol=2e-8)
+        np.testing.assert_allclose(g["dW3"][e], fd(W3[e]), rtol=2e-6, atol=2e-8)
         np.testing.assert_allclose(g["dW2"][e], fd(W2[e]), rtol=2e-6, atol=2e-8)
 
 
