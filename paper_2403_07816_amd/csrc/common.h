@@ -61,6 +61,17 @@ template <> struct RowVec<bf16_t, 8> {
     *reinterpret_cast<u32x4*>(p) =
         u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
   }
+  // the same, streamed past the caches (data that is read or written exactly once)
+  static __device__ __forceinline__ void ld_stream(const bf16_t* p, float* v) {
+    const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo(w[i]); v[2 * i + 1] = bf16hi(w[i]); }
+  }
+  static __device__ __forceinline__ void st_stream(bf16_t* p, const float* v) {
+    __builtin_nontemporal_store(
+        u32x4{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])},
+        reinterpret_cast<u32x4*>(p));
+  }
 };
 template <> struct RowVec<float, 8> {
   static __device__ __forceinline__ void ld(const float* p, float* v) {
@@ -71,6 +82,16 @@ template <> struct RowVec<float, 8> {
   static __device__ __forceinline__ void st(float* p, const float* v) {
     *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
     *reinterpret_cast<f32x4*>(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+  }
+  static __device__ __forceinline__ void ld_stream(const float* p, float* v) {
+    const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + 4));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+  static __device__ __forceinline__ void st_stream(float* p, const float* v) {
+    __builtin_nontemporal_store(f32x4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f32x4*>(p));
+    __builtin_nontemporal_store(f32x4{v[4], v[5], v[6], v[7]}, reinterpret_cast<f32x4*>(p + 4));
   }
 };
 

@@ -7,6 +7,7 @@
 //   dwr_partial     dW_router = x^T ds as per-token-chunk partial sums
 //   dwr_reduce      fixed-order sum of the partials (and of db_router)
 //   dx_finish       dX[t] = sum_j dxs[inv_pos[t,j]] + ds[t] W_router^T, W_router slice kept in registers
+// The rows these kernels stream (x, dxs, dX) are touched once per kernel and go past the caches.
 // dwr_partial and dx_finish work expert-major (partials [chunk][E][d], W_router as [E,d]): a
 // lane's 8 columns of one expert are then 32 contiguous bytes instead of 8 pieces E floats apart.
 #include "common.h"
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void dwr_partial_kernel(const XT* __restrict__
     for (int q = 0; q < nt; q += 4) {
       float xv[4][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) RowVec<XT, 8>::ld(x + (size_t)min(t0 + q + u, T - 1) * d + c0, xv[u]);
+      for (int u = 0; u < 4; ++u) RowVec<XT, 8>::ld_stream(x + (size_t)min(t0 + q + u, T - 1) * d + c0, xv[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ d
         const int t = t0 + tq + q;
         const int r = t < T ? inv_pos[(size_t)t * k + j] : -1;
         have[q] = r >= 0;
-        RowVec<XT, 8>::ld(dxs + (size_t)max(r, 0) * d + c0, v[q]);
+        RowVec<XT, 8>::ld_stream(dxs + (size_t)max(r, 0) * d + c0, v[q]);
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q)
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ d
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (t0 + tq + q < T) RowVec<XT, 8>::st(dX + (size_t)(t0 + tq + q) * d + c0, acc[q]);
+      if (t0 + tq + q < T) RowVec<XT, 8>::st_stream(dX + (size_t)(t0 + tq + q) * d + c0, acc[q]);
   }
 }
 
