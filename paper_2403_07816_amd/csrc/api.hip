@@ -21,7 +21,7 @@ struct Carver {
 inline int esize(int dtype) { return dtype == BTX_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dtype) { return dtype == BTX_F32 || dtype == BTX_BF16; }
 
-struct FwdWs { void *xs, *act, *y, *h1, *h3; size_t bytes; };
+struct FwdWs { void *xs, *act, *y, *h1, *h3, *partial; size_t bytes; };
 FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype, bool save) {
   const size_t R = (size_t)T * k, es = esize(dtype);
   Carver c(ws);
@@ -34,11 +34,13 @@ FwdWs carve_forward(void* ws, int T, int d, int f, int k, int dtype, bool save) 
   const bool own_h = !save && ff_up_needs_h(dtype, d, f);
   w.h1 = own_h ? c.take(R * f * es) : nullptr;
   w.h3 = own_h ? c.take(R * f * es) : nullptr;
+  const size_t split = ff_split_bytes(dtype, d, f);      // K slices of DOWN's last round
+  w.partial = split ? c.take(split) : nullptr;
   w.bytes = c.used;
   return w;
 }
 
-struct BwdWs { void *xs, *dysT, *dys, *dh1, *dh3, *ga, *dxs, *scratch, *router; float* dg_part; size_t bytes; };
+struct BwdWs { void *xs, *dysT, *dys, *dh1, *dh3, *ga, *dxs, *scratch, *router, *partial; float* dg_part; size_t bytes; };
 BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   const size_t R = (size_t)T * k, es = esize(dtype);
   Carver c(ws);
@@ -57,6 +59,8 @@ BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   w.dg_part = static_cast<float*>(c.take(R * (size_t)bwd_act_partials(dtype, f) * sizeof(float)));
   w.scratch = c.take(ff_scratch_bytes(dtype, (int)R, f));
   w.router = c.take(router_bwd_workspace_bytes(T, d, E));
+  const size_t split = ff_split_bytes(dtype, d, f);      // K slices of BWD_DX's last round
+  w.partial = split ? c.take(split) : nullptr;
   w.bytes = c.used;
   return w;
 }
@@ -265,7 +269,7 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   if (!fused) BTX_STAGE(BTX_STAGE_GATHER_X, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
   const RowSource xs = fused ? RowSource{x, perm, k} : RowSource{w.xs, nullptr, 1};
   BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
-  BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, s));
+  BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, w.partial, s));
   BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, residual, out, T, k, d, dtype, s));
   return BTX_OK;
 }
@@ -311,7 +315,7 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   const RowSource dys = fused ? RowSource{dY, perm, k} : RowSource{w.dys, nullptr, 1};
   BTX_STAGE(BTX_STAGE_BWD_ACT, launch_bwd_act(dtype, dys, W2, save_h1, save_h3, gates, perm, offsets, sh, w.dh1,
                                               w.dh3, w.ga, n_dw == 3, w.dg_part, w.scratch, s));
-  BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, s));
+  BTX_STAGE(BTX_STAGE_BWD_DX, launch_bwd_dx(dtype, w.dh1, w.dh3, W1, W3, offsets, sh, w.dxs, w.partial, s));
   if (n_dw == 3) {
     const bool tr = ff_dw_transposed(dtype, d, f);
     auto gather_dw_operands = [&]() -> int {

@@ -250,8 +250,11 @@ bool ff_up_needs_h(int dtype, int d, int f);
 int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* scratch, hipStream_t s);
 // y = act W2
+// partial: ff_split_bytes() of scratch (the bf16 MFMA path cuts the tiles of a partly filled last round along K
+// and adds the slices in a second kernel); may be NULL when ff_split_bytes() is 0
+size_t ff_split_bytes(int dtype, int d, int f);
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
-                hipStream_t s);
+                void* partial, hipStream_t s);
 // D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a.
 // dh1, dh3: [R,f].  When ff_dw_transposed() holds, `ga` receives g*a transposed and padded
 // ([f][ff_dw_pitch()]), or nothing at all when want_dw is false; otherwise ga is [R,f].
@@ -261,7 +264,7 @@ int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* 
                    bool want_dw, float* dg_part, void* scratch, hipStream_t s);
 // dxs = dh1 W1^T + dh3 W3^T
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
-                  const FfShapes& sh, void* dxs, hipStream_t s);
+                  const FfShapes& sh, void* dxs, void* partial, hipStream_t s);
 // dW1 = xs^T dh1, dW3 = xs^T dh3, dW2 = ga^T dys, per expert over its rows.  When
 // ff_dw_transposed() holds, xs, dys and ga are passed in the transposed, padded form with
 // pitch ff_dw_pitch() (xs and dys as launch_gather_rows_t writes them, ga as launch_bwd_act

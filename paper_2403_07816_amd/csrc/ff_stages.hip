@@ -37,9 +37,11 @@ int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void*
   if (xs.perm) return BTX_ERR_UNSUPPORTED;  // the plain path takes gathered rows
   return generic_up_swiglu(dtype, xs.base, W1, W3, offsets, sh, h1, h3, act, s);
 }
+size_t ff_split_bytes(int dtype, int d, int f) { return dtype == BTX_BF16 && mfma_shape(d, f) ? mfma_split_bytes() : 0; }
+
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
-                hipStream_t s) {
-  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_down(act, W2, offsets, sh, y, s);
+                void* partial, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_down(act, W2, offsets, sh, y, partial, s);
   return generic_down(dtype, act, W2, offsets, sh, y, s);
 }
 int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
@@ -52,8 +54,8 @@ int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* 
   return generic_bwd_act(dtype, dys.base, W2, h1, h3, gates, perm, offsets, sh, dh1, dh3, ga, dg_part, scratch, s);
 }
 int launch_bwd_dx(int dtype, const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* offsets,
-                  const FfShapes& sh, void* dxs, hipStream_t s) {
-  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dx(dh1, dh3, W1, W3, offsets, sh, dxs, s);
+                  const FfShapes& sh, void* dxs, void* partial, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_bwd_dx(dh1, dh3, W1, W3, offsets, sh, dxs, partial, s);
   return generic_bwd_dx(dtype, dh1, dh3, W1, W3, offsets, sh, dxs, s);
 }
 int launch_bwd_dw13(int dtype, int dW_dtype, const void* xs, const void* dh1, const void* dh3, const int32_t* offsets,

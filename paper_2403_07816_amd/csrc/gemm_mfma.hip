@@ -38,6 +38,7 @@ namespace {
 // supertile: row tiles x column tiles that run concurrently chip-wide, and the XCDs along its
 // rows (8 / kXcdM along its columns)
 constexpr int kSupM = 16, kSupN = 16, kXcdM = 4;
+constexpr int kSplitMaxCus = 256;   // compute units the K-cut of a last round is laid out for (see Gemm::split_plan)
 static_assert(kSupM % kXcdM == 0 && 8 % kXcdM == 0 && kSupN % (8 / kXcdM) == 0 && (kSupM * kSupN) % 8 == 0, "supertile");
 
 enum Mode { UP = 0, DOWN = 1, BWD_ACT = 2, BWD_DX = 3, DW13 = 4, DW2 = 5 };
@@ -58,6 +59,9 @@ struct MArgs {
   int tiles_n, tiles_m;                 // tile grid (tiles_m is the worst case for grouped-M)
   int c_is_f32;
   int blocks_per_e;                     // grouped-K: block ids per expert (a multiple of 8)
+  int total_ids;                        // tile ids of the launch (a few name no tile: padding of the id space)
+  // DOWN / BWD_DX: the tiles of the last, partly filled round are cut along K (see Gemm::split_plan)
+  f32x4* partial; int cus;              // fp32 accumulators of the slices (NULL: never cut); compute units
 };
 
 __device__ __forceinline__ void wait_vmcnt(int n) {
@@ -196,42 +200,44 @@ struct Gemm {
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 
-  static __device__ void run(const MArgs& g, char* smem) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int wm = wave / WN, wn = wave % WN;
-
-    // ---- which tile ------------------------------------------------------
-    // Workgroups are dealt round-robin to the 8 XCDs (block id mod 8) and start in id order.
-    // SM x SN consecutive ids form one supertile of the tile grid, so that the tiles running at
-    // any moment share few operand panels chip-wide (little HBM / infinity-cache traffic, short
-    // miss latency); inside it XCD x owns a (SM/XM) x (SN/XN) sub-block, so that the panels its
-    // CUs stream meet in that XCD's L2.  Only whole supertiles are laid out like this.  The
-    // tiles right of and below the last whole supertile form one list (right strip row by row,
-    // then the bottom strip column by column) that is cut into 8 equal runs, one per XCD: a
-    // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
-    // tiles of the row-grouped products depends on the routing and is counted here.
-    constexpr int SM = kSupM, SN = kSupN, XM = kXcdM, XN = 8 / XM;
-    // Row-grouped products: the experts' row ranges are looked at by the whole wavefront at once, lane x
-    // taking expert x (at most 64): one load and two prefix sums instead of loops of dependent scalar
-    // loads over the experts, which with 32 experts took longer than a tenth of a short tile's main loop.
-    // (The products grouped along K know their expert from the block id and keep the one short loop.)
-    int x_o0 = 0, x_o1 = 0, x_nt = 0, x_pad = 0, x_nt_incl = 0, x_pad_incl = 0;
-    int n_rt = g.tiles_m;
-    if (!GROUP_K) {
-      const int xe = min(lane, g.E - 1);
-      x_o0 = g.offsets[xe];
-      x_o1 = g.offsets[xe + 1];
-      const int x_n = lane < g.E ? x_o1 - x_o0 : 0;
-      x_nt = (x_n + BM - 1) / BM;
-      x_pad = (x_n + 63) & ~63;
-      x_nt_incl = wave_incl_scan_i32(x_nt, lane);                              // row tiles up to and including expert x
-      if (MODE == BWD_ACT) x_pad_incl = wave_incl_scan_i32(x_pad, lane);       // padded rows likewise
-      n_rt = __builtin_amdgcn_readlane(x_nt_incl, kWave - 1);
+  // ---- which tile ------------------------------------------------------
+  // Workgroups are dealt round-robin to the 8 XCDs (block id mod 8) and start in id order.
+  // SM x SN consecutive ids form one supertile of the tile grid, so that the tiles running at
+  // any moment share few operand panels chip-wide (little HBM / infinity-cache traffic, short
+  // miss latency); inside it XCD x owns a (SM/XM) x (SN/XN) sub-block, so that the panels its
+  // CUs stream meet in that XCD's L2.  Only whole supertiles are laid out like this.  The
+  // tiles right of and below the last whole supertile form one list (right strip row by row,
+  // then the bottom strip column by column) that is cut into 8 equal runs, one per XCD: a
+  // ragged edge must not leave some XCDs with fewer tiles than others.  The number of row
+  // tiles of the row-grouped products depends on the routing and is counted here.
+  struct Tile { int e, row0, row_end, k_begin, k_end, kp_begin, tile_n, exp_row0; };
+  // Row-grouped products: the experts' row ranges are looked at by the whole wavefront at once, lane x
+  // taking expert x (at most 64): one load and two prefix sums instead of loops of dependent scalar
+  // loads over the experts, which with 32 experts took longer than a tenth of a short tile's main loop.
+  // (The products grouped along K know their expert from the block id and keep the one short loop.)
+  struct Experts {
+    int o0, o1, nt, pad, nt_incl, pad_incl, n_rt;
+    __device__ __forceinline__ Experts(const MArgs& g, int lane) : o0(0), o1(0), nt(0), pad(0), nt_incl(0), pad_incl(0) {
+      n_rt = g.tiles_m;
+      if (!GROUP_K) {
+        const int xe = min(lane, g.E - 1);
+        o0 = g.offsets[xe];
+        o1 = g.offsets[xe + 1];
+        const int x_n = lane < g.E ? o1 - o0 : 0;
+        nt = (x_n + BM - 1) / BM;
+        pad = (x_n + 63) & ~63;
+        nt_incl = wave_incl_scan_i32(nt, lane);                              // row tiles up to and including expert x
+        if (MODE == BWD_ACT) pad_incl = wave_incl_scan_i32(pad, lane);       // padded rows likewise
+        n_rt = __builtin_amdgcn_readlane(nt_incl, kWave - 1);
+      }
     }
+  };
+  // tile id -> tile; false: the id names no tile (all 64 lanes must be active)
+  static __device__ __forceinline__ bool locate(const MArgs& g, const Experts& x, int id, Tile& t) {
+    constexpr int SM = kSupM, SN = kSupN, XM = kXcdM, XN = 8 / XM;
+    const int n_rt = x.n_rt;
     const int fr = n_rt / SM, fc = g.tiles_n / SN;     // whole supertile rows / columns
     const int blocks_full = fr * fc * SM * SN;
-    int id = blockIdx.x;
     int e = 0;
     if (GROUP_K) {
       e = id / g.blocks_per_e;
@@ -249,7 +255,7 @@ struct Gemm {
       const int n_right = fr * SM * w, n_left = n_right + h * g.tiles_n;
       const int run = (n_left + 7) / 8;
       const int l = (idl % 8) * run + idl / 8;
-      if (idl / 8 >= run || l >= n_left) return;
+      if (idl / 8 >= run || l >= n_left) return false;
       if (l < n_right) {
         tile_m = l / w;
         tile_n = fc * SN + l % w;
@@ -258,28 +264,116 @@ struct Gemm {
         tile_n = (l - n_right) / h;
       }
     }
-
-    int row0, row_end, k_begin, k_end;
-    int kp_begin = 0;                                   // first padded row of expert e (transposed operand)
+    t.kp_begin = 0;                                     // first padded row of expert e (transposed operand)
+    t.exp_row0 = 0;
     if (GROUP_K) {
-      row0 = tile_m * BM;
-      row_end = g.M;
-      k_begin = g.offsets[e];
-      k_end = g.offsets[e + 1];
-      for (int x = 0; x < e; ++x) kp_begin += (g.offsets[x + 1] - g.offsets[x] + 63) & ~63;
+      t.row0 = tile_m * BM;
+      t.row_end = g.M;
+      t.k_begin = g.offsets[e];
+      t.k_end = g.offsets[e + 1];
+      for (int q = 0; q < e; ++q) t.kp_begin += (g.offsets[q + 1] - g.offsets[q] + 63) & ~63;
     } else {
       // the expert whose row tiles include tile_m: the first lane whose running total exceeds it
-      const unsigned long long owners = __ballot(x_nt_incl > tile_m);
-      if (owners == 0) return;                          // past the last row tile of this routing
+      const unsigned long long owners = __ballot(x.nt_incl > tile_m);
+      if (owners == 0) return false;                    // past the last row tile of this routing
       e = __ffsll((long long)owners) - 1;
-      const int t = tile_m - (__builtin_amdgcn_readlane(x_nt_incl, e) - __builtin_amdgcn_readlane(x_nt, e));
-      row0 = __builtin_amdgcn_readlane(x_o0, e) + t * BM;
-      row_end = __builtin_amdgcn_readlane(x_o1, e);
-      k_begin = 0;
-      k_end = g.K;
+      const int tt = tile_m - (__builtin_amdgcn_readlane(x.nt_incl, e) - __builtin_amdgcn_readlane(x.nt, e));
+      t.exp_row0 = __builtin_amdgcn_readlane(x.o0, e);
+      t.row0 = t.exp_row0 + tt * BM;
+      t.row_end = __builtin_amdgcn_readlane(x.o1, e);
+      t.k_begin = 0;
+      t.k_end = g.K;
     }
     if (MODE == BWD_ACT)                                // where expert e starts in the transposed, padded output
-      kp_begin = __builtin_amdgcn_readlane(x_pad_incl, e) - __builtin_amdgcn_readlane(x_pad, e);
+      t.kp_begin = __builtin_amdgcn_readlane(x.pad_incl, e) - __builtin_amdgcn_readlane(x.pad, e);
+    t.e = e;
+    t.tile_n = tile_n;
+    return true;
+  }
+
+  // DOWN and BWD_DX have few, long tiles (16 column tiles): their last round is often a small fraction of
+  // the chip (8.25 rounds for the benchmark's top-2 layer, 4.1 for top-1, 2.25 for one sequence), and a
+  // tile cannot be cut smaller.  So the tiles of that round are cut along K instead: slice s of a
+  // left-over tile runs k tiles [s nk/S, (s+1) nk/S) in a workgroup of its own and leaves its fp32
+  // accumulators in `partial`; a second, small kernel adds the S slices of a tile in slice order and stores
+  // the result.  No atomics, and the order of every sum is fixed by the shapes and the number of compute
+  // units alone.  ids >= total_ids are the workgroups of the slices 1 .. S-1.
+  static constexpr bool SPLIT = (MODE == DOWN || MODE == BWD_DX);
+  static constexpr int kMaxSlices = 4, kMinSliceTiles = 16, kIdHoles = 8;   // the id space has up to 8 ids past the last tile
+  struct SplitPlan { int id_full, n_left, n_slices; };
+  static __device__ __forceinline__ SplitPlan split_plan(const MArgs& g, int n_rt) {
+    SplitPlan p{0, 0, 1};
+    if (!SPLIT || !g.partial) return p;
+    const int n_real = n_rt * g.tiles_n;
+    p.id_full = n_real / g.cus * g.cus;                 // ids below this fill whole rounds
+    const int left = n_real - p.id_full;
+    if (left == 0) return p;
+    p.n_left = left + kIdHoles;                         // ids id_full .. id_full + n_left - 1 may name a tile
+    // as many slices as fill the chip, at most four, none shorter than kMinSliceTiles k tiles (a slice pays a
+    // tile's fixed costs once more, and its accumulators travel through memory)
+    const int nk_all = (g.K + BK - 1) / BK * (MODE == BWD_DX ? 2 : 1);
+    p.n_slices = max(1, min(min(kMaxSlices, g.cus / left), nk_all / kMinSliceTiles));
+    return p;
+  }
+  // fp32 accumulators of (left-over tile j, slice s), as the wavefronts hold them: [wave][fragment][lane] x 4
+  static __device__ __forceinline__ f32x4* partial_slot(const MArgs& g, const SplitPlan& p, int j, int slice) {
+    return g.partial + (size_t)(j * p.n_slices + slice) * (NW * TM * TN * kWave);
+  }
+
+  // Second kernel of a K-cut product: one workgroup per left-over tile adds the slices' accumulators in
+  // slice order and stores the tile (same ownership of the elements as in run(): fragment (i, j) of a
+  // wavefront, lane l = row l % 16, four columns from 4 (l / 16)).
+  static __device__ void finish(const MArgs& g) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wm = wave / WN, wn = wave % WN;
+    const Experts experts(g, lane);
+    const SplitPlan plan = split_plan(g, experts.n_rt);
+    const int j = blockIdx.x;
+    if (plan.n_slices <= 1 || j >= plan.n_left) return;
+    Tile tile;
+    if (!locate(g, experts, plan.id_full + j, tile)) return;
+    const int col0 = tile.tile_n * BNH;
+    bf16_t* C = static_cast<bf16_t*>(g.C0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int jj = 0; jj < TN; ++jj) {
+        const size_t at = (size_t)wave * (TM * TN * kWave) + (i * TN + jj) * kWave + lane;
+        f32x4 sum = __builtin_nontemporal_load(partial_slot(g, plan, j, 0) + at);
+        for (int sl = 1; sl < plan.n_slices; ++sl) {
+          const f32x4 v = __builtin_nontemporal_load(partial_slot(g, plan, j, sl) + at);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) sum[x] += v[x];
+        }
+        const int m = tile.row0 + wm * (TM * 16) + i * 16 + (lane & 15);
+        const int n = col0 + wn * (TNH * 16) + (jj % TNH) * 16 + 4 * (lane >> 4);
+        if (m < tile.row_end && n < g.N)
+          *reinterpret_cast<u32x2*>(C + (size_t)m * g.ldc + n) =
+              u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+      }
+  }
+
+  static __device__ void run(const MArgs& g, char* smem) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const Experts experts(g, lane);
+    const SplitPlan plan = split_plan(g, experts.n_rt);
+    int id = blockIdx.x, slice = 0;
+    if (SPLIT && id >= g.total_ids) {                    // a workgroup for slice 1.. of a left-over tile
+      if (plan.n_slices <= 1) return;
+      const int w = id - g.total_ids;
+      slice = 1 + w / plan.n_left;
+      if (slice >= plan.n_slices) return;
+      id = plan.id_full + w % plan.n_left;
+    }
+    const bool sliced = SPLIT && plan.n_slices > 1 && id >= plan.id_full;
+    Tile tile;
+    if (!locate(g, experts, id, tile)) return;
+    const int e = tile.e, row0 = tile.row0, row_end = tile.row_end, k_begin = tile.k_begin, k_end = tile.k_end;
+    const int kp_begin = tile.kp_begin, tile_n = tile.tile_n;
     const int col0 = tile_n * BNH;
 
     const bf16_t* Bp0 = g.B0;
@@ -328,20 +422,27 @@ struct Gemm {
 
     const int k_len = k_end - k_begin;
     const int nk1 = (k_len + BK - 1) / BK;
-    const int nk = MODE == BWD_DX ? 2 * nk1 : nk1;
+    const int nk_all = MODE == BWD_DX ? 2 * nk1 : nk1;
+    // a slice runs k tiles kb .. kb + nk - 1 of the tile's nk_all; below, kt counts from the slice's first one
+    const int kb = sliced ? slice * nk_all / plan.n_slices : 0;
+    const int nk = sliced ? (slice + 1) * nk_all / plan.n_slices - kb : nk_all;
     // K is a multiple of 32 (of 64 in the dW products, whose rows are padded): when it is not
     // a multiple of 64 the last k tile of a pass is half empty.  Its copies are re-pointed at
     // the valid half (any finite data will do) and the A fragments of its second half are
     // zeroed in registers, so those k steps add nothing.
     // TAIL is a template parameter: the common shapes pay nothing for it.
     static_assert(!(TAIL && GROUP_K), "the dW products have no K tail");
-    auto is_tail = [&](int kt) { return TAIL && (kt == nk1 - 1 || kt == nk - 1); };
+    // in the slice's own count of k tiles: where the second K pass begins, and the two possible tail tiles
+    const int pass2_at = nk1 - kb, tail1_at = nk1 - 1 - kb, tail2_at = nk_all - 1 - kb;
+    const int k_first1 = k_begin + kb * BK, k_first2 = k_begin - pass2_at * BK;
+    const int kp_first = kp_begin + kb * BK;
+    auto is_tail = [&](int kt) { return TAIL && (kt == tail1_at || kt == tail2_at); };
     const uint32_t smem_base = (uint32_t)(uintptr_t)smem;   // LDS byte address of the dynamic segment
 
     // Copies of the A / B part of tile kt into LDS stage kt % NSA / kt % NSB.
     auto tile_k0 = [&](int kt, bool kc, bool& pass2) {
-      pass2 = MODE == BWD_DX && kt >= nk1;
-      return (GROUP_K && kc ? kp_begin : k_begin) + (pass2 ? kt - nk1 : kt) * BK;
+      pass2 = MODE == BWD_DX && kt >= pass2_at;
+      return (GROUP_K && kc ? kp_first : (pass2 ? k_first2 : k_first1)) + kt * BK;
     };
     auto issueA = [&](int kt) {
       bool pass2;
@@ -439,6 +540,9 @@ struct Gemm {
         __builtin_amdgcn_s_barrier();                // tile 0 published
       }
       if (grp == 1 && nk > 0) __builtin_amdgcn_s_barrier();   // idle during group 0's first memory phase
+      // one k tile per trip: unrolled by two (the compiler's choice for some instantiations) the loop ran 2 to
+      // 4 % slower
+#pragma unroll 1
       for (int kt = 0; kt < nk; ++kt) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -469,6 +573,15 @@ struct Gemm {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+    }
+
+    if (SPLIT && sliced) {                               // a slice leaves its accumulators for split_finish
+      f32x4* slot = partial_slot(g, plan, id - plan.id_full, slice) + (size_t)wave * (TM * TN * kWave);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) __builtin_nontemporal_store(acc[i][j], slot + (i * TN + j) * kWave + lane);
+      return;
     }
 
     // ---- epilogue ----------------------------------------------------------
@@ -586,7 +699,7 @@ struct Gemm {
           // scattered 16-byte stores cost the address unit four times as much.  Rows past the
           // group's end are zeros (see the gate above) and are written up to the 64-row padding.
           typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-          const int o_e = __builtin_amdgcn_readlane(x_o0, e);
+          const int o_e = tile.exp_row0;
           const int pad_e = (row_end - o_e + 63) & ~63;
           const int fr = 8 * lane_c + (lane_m >> 2), fa4 = lane_m & 3;
           const int qc = lane >> 2, qg = lane & 3;        // read-back view: column within 16, 8-row chunk
@@ -715,6 +828,24 @@ __global__ __launch_bounds__(WM* WN* kWave) void mfma_gemm_kernel(MArgs g) {
   Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>::run(g, smem);
 }
 
+template <int BM, int BN, int BK, int WM, int WN, int NSA, int NSB, int MODE, bool TAIL = false>
+__global__ __launch_bounds__(WM* WN* kWave) void mfma_split_finish_kernel(MArgs g) {
+  Gemm<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>::finish(g);
+}
+
+// compute units of the current device (looked up once per device)
+int compute_units() {
+  static int n[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+  if (n[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8) return -1;
+    n[dev] = v;
+  }
+  return n[dev];
+}
+
 // The kernels use more dynamic LDS than the default limit allows: the limit is raised once per
 // device and instantiation (idempotent, so a race between threads is harmless).  This must not
 // happen inside a stream capture; mfma_prepare() does it for every instantiation up front.
@@ -742,10 +873,30 @@ int launch(MArgs g, hipStream_t s) {
   g.tiles_m = G::GROUP_K ? ceil_div(g.M, BM) : ceil_div(g.R, BM) + g.E;
   // every tile has exactly one block id below (number of tiles) + 8; see the tile mapping
   g.blocks_per_e = (int)align_up((size_t)g.tiles_m * g.tiles_n, 8) + 8;
-  const int total = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
+  g.total_ids = G::GROUP_K ? g.E * g.blocks_per_e : g.tiles_m * g.tiles_n + 8;
   if (int rc = raise_lds_limit<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>()) return rc;
-  mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL><<<total, G::NT, G::LDS_BYTES, s>>>(g);
+  int grid = g.total_ids;
+  if constexpr (G::SPLIT) {
+    // K too short for two slices of the minimum length: split_plan() would never cut
+    if (ceil_div(g.K, BK) * (MODE == BWD_DX ? 2 : 1) < 2 * G::kMinSliceTiles) g.partial = nullptr;
+    if (g.partial) {                                   // room for the workgroups of slices 1.. of the last round
+      g.cus = compute_units();
+      if (g.cus <= 0) return BTX_ERR_HIP;
+      if (g.cus > kSplitMaxCus) g.partial = nullptr;   // the caller's buffer is sized for that many
+      else grid += g.cus + G::kIdHoles * (G::kMaxSlices - 1);   // (left + 8)(S - 1) <= cus + 8 (S - 1) for every left
+    }
+  } else {
+    g.partial = nullptr;
+  }
+  mfma_gemm_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL><<<grid, G::NT, G::LDS_BYTES, s>>>(g);
   BTX_LAUNCH_CHECK();
+  if constexpr (G::SPLIT) {
+    if (g.partial) {
+      mfma_split_finish_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>
+          <<<g.cus / 2 + G::kIdHoles, G::NT, 0, s>>>(g);
+      BTX_LAUNCH_CHECK();
+    }
+  }
   return BTX_OK;
 }
 
@@ -756,6 +907,10 @@ bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh
 }  // namespace
 
 constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
+
+// fp32 accumulators of the K slices of DOWN / BWD_DX's last round: at most cus + 8 * 4 (tile, slice) pairs
+// of 256 x 256 floats
+size_t mfma_split_bytes() { return (size_t)(kSplitMaxCus + 32) * 256 * 256 * sizeof(float); }
 
 int mfma_prepare() {
   int rc = BTX_OK;
@@ -787,10 +942,11 @@ int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const in
   return sh.d % 64 ? launch<256, 256, 64, 2, 4, 3, 2, UP, true>(g, s) : launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s);
 }
 
-int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, hipStream_t s) {
+int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, void* partial,
+              hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y;
+  g.A0 = (const bf16_t*)act; g.B0 = (const bf16_t*)W2; g.C0 = y; g.partial = (f32x4*)partial;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.d; g.ldc = sh.d;
   g.strideB_e = sh.s2; g.R = sh.R;
   return sh.f % 64 ? launch<256, 256, 64, 2, 4, 3, 2, DOWN, true>(g, s) : launch<256, 256, 64, 2, 4, 3, 2, DOWN>(g, s);
@@ -813,10 +969,10 @@ int mfma_bwd_act(const RowSource& dys, const void* W2, const void* h1, const voi
 }
 
 int mfma_bwd_dx(const void* dh1, const void* dh3, const void* W1, const void* W3, const int32_t* off,
-                const FfShapes& sh, void* dxs, hipStream_t s) {
+                const FfShapes& sh, void* dxs, void* partial, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)dh1; g.A1 = (const bf16_t*)dh3; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = dxs;
+  g.A0 = (const bf16_t*)dh1; g.A1 = (const bf16_t*)dh3; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = dxs; g.partial = (f32x4*)partial;
   g.offsets = off; g.E = sh.E; g.N = sh.d; g.K = sh.f; g.lda = sh.f; g.ldb = sh.f; g.ldc = sh.d;
   g.strideB_e = sh.s13; g.R = sh.R;
   return sh.f % 64 ? launch<256, 256, 64, 2, 4, 3, 2, BWD_DX, true>(g, s)

@@ -208,6 +208,22 @@ def test_bf16_random_shapes_on_the_mfma_path(case):
                         dW_dtype=F32 if case % 3 == 0 else None)
 
 
+@pytest.mark.parametrize("T,d,f,E,k,kw", [
+    # 12 tiles in a round of 256 workgroups, f = 32.5 k tiles: the down projection is cut in two, the
+    # input-gradient product (two K passes, 66 k tiles, a half-empty tile at the end of each) in four
+    (700, 320, 2080, 3, 2, {}),
+    # top-1 with dropped pairs: rows of the output nothing writes, tiles of unequal height
+    (900, 256, 2048, 4, 1, dict(mode=B.BTX_ROUTE_SWITCH_TOP1, bias=[2.0, 0, 0, 0], cf=1.5)),
+    # 96 tiles left over: two slices; 192 left over: too many to cut (the extra workgroups find nothing to do)
+    (600, 4096, 1024, 3, 2, {}),
+    (1100, 4096, 1024, 4, 2, {}),
+])
+def test_bf16_last_round_cut_along_k(T, d, f, E, k, kw):
+    """DOWN and BWD_DX cut the tiles of a partly filled last round along K when K is long enough
+    (f >= 2048 / f >= 1024) and add the slices in a second kernel."""
+    run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True, poison=True, **kw)
+
+
 def test_bf16_unrelated_experts_meet_the_plain_bar_on_router_gradients():
     """With experts that share nothing the gate Jacobian has no cancellation and
     dW_router / db_router must meet 2e-2 without any amplification factor."""
