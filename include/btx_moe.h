@@ -27,7 +27,7 @@
  *   - Every kernel is free of atomics: results are bit-identical run to run.  The order
  *     of every sum is fixed by the shapes, the routing counts and the number of compute
  *     units of the device (the bf16 down-projection and input-gradient products cut the
- *     tiles of a partly filled last round of workgroups into up to four K ranges, added in
+ *     tiles of a partly filled last round of workgroups into up to eight K ranges, added in
  *     ascending order by a second kernel).
  *   - Outputs must not alias inputs unless stated.  NaN/Inf inputs give
  *     unspecified results.

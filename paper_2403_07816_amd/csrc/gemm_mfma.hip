@@ -38,6 +38,7 @@ namespace {
 // supertile: row tiles x column tiles that run concurrently chip-wide, and the XCDs along its
 // rows (8 / kXcdM along its columns)
 constexpr int kSupM = 16, kSupN = 16, kXcdM = 4;
+constexpr int kSplitMaxSlices = 8;
 constexpr int kSplitMaxCus = 256;   // compute units the K-cut of a last round is laid out for (see Gemm::split_plan)
 static_assert(kSupM % kXcdM == 0 && 8 % kXcdM == 0 && kSupN % (8 / kXcdM) == 0 && (kSupM * kSupN) % 8 == 0, "supertile");
 
@@ -299,7 +300,7 @@ struct Gemm {
   // the result.  No atomics, and the order of every sum is fixed by the shapes and the number of compute
   // units alone.  ids >= total_ids are the workgroups of the slices 1 .. S-1.
   static constexpr bool SPLIT = (MODE == DOWN || MODE == BWD_DX);
-  static constexpr int kMaxSlices = 4, kMinSliceTiles = 16, kIdHoles = 8;   // the id space has up to 8 ids past the last tile
+  static constexpr int kMaxSlices = kSplitMaxSlices, kMinSliceTiles = 16, kIdHoles = 8;   // the id space has up to 8 ids past the last tile
   struct SplitPlan { int id_full, n_left, n_slices; };
   static __device__ __forceinline__ SplitPlan split_plan(const MArgs& g, int n_rt) {
     SplitPlan p{0, 0, 1};
@@ -309,7 +310,7 @@ struct Gemm {
     const int left = n_real - p.id_full;
     if (left == 0) return p;
     p.n_left = left + kIdHoles;                         // ids id_full .. id_full + n_left - 1 may name a tile
-    // as many slices as fill the chip, at most four, none shorter than kMinSliceTiles k tiles (a slice pays a
+    // as many slices as fill the chip, at most eight, none shorter than kMinSliceTiles k tiles (a slice pays a
     // tile's fixed costs once more, and its accumulators travel through memory)
     const int nk_all = (g.K + BK - 1) / BK * (MODE == BWD_DX ? 2 : 1);
     p.n_slices = max(1, min(min(kMaxSlices, g.cus / left), nk_all / kMinSliceTiles));
@@ -320,38 +321,37 @@ struct Gemm {
     return g.partial + (size_t)(j * p.n_slices + slice) * (NW * TM * TN * kWave);
   }
 
-  // Second kernel of a K-cut product: one workgroup per left-over tile adds the slices' accumulators in
-  // slice order and stores the tile (same ownership of the elements as in run(): fragment (i, j) of a
-  // wavefront, lane l = row l % 16, four columns from 4 (l / 16)).
+  // Second kernel of a K-cut product: TM workgroups per left-over tile (one per fragment row of the
+  // wavefronts: a single workgroup per tile left most of the chip idle and took 53 us for 72 MB) add the
+  // slices' accumulators in slice order and store the tile (same ownership of the elements as in run():
+  // fragment (i, j) of a wavefront, lane l = row l % 16, four columns from 4 (l / 16)).
   static __device__ void finish(const MArgs& g) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int wm = wave / WN, wn = wave % WN;
     const Experts experts(g, lane);
     const SplitPlan plan = split_plan(g, experts.n_rt);
-    const int j = blockIdx.x;
+    const int j = blockIdx.x / TM, i = blockIdx.x % TM;
     if (plan.n_slices <= 1 || j >= plan.n_left) return;
     Tile tile;
     if (!locate(g, experts, plan.id_full + j, tile)) return;
     const int col0 = tile.tile_n * BNH;
     bf16_t* C = static_cast<bf16_t*>(g.C0);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int jj = 0; jj < TN; ++jj) {
+      const size_t at = (size_t)wave * (TM * TN * kWave) + (i * TN + jj) * kWave + lane;
+      f32x4 sum = __builtin_nontemporal_load(partial_slot(g, plan, j, 0) + at);
+      for (int sl = 1; sl < plan.n_slices; ++sl) {
+        const f32x4 v = __builtin_nontemporal_load(partial_slot(g, plan, j, sl) + at);
 #pragma unroll
-      for (int jj = 0; jj < TN; ++jj) {
-        const size_t at = (size_t)wave * (TM * TN * kWave) + (i * TN + jj) * kWave + lane;
-        f32x4 sum = __builtin_nontemporal_load(partial_slot(g, plan, j, 0) + at);
-        for (int sl = 1; sl < plan.n_slices; ++sl) {
-          const f32x4 v = __builtin_nontemporal_load(partial_slot(g, plan, j, sl) + at);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) sum[x] += v[x];
-        }
-        const int m = tile.row0 + wm * (TM * 16) + i * 16 + (lane & 15);
-        const int n = col0 + wn * (TNH * 16) + (jj % TNH) * 16 + 4 * (lane >> 4);
-        if (m < tile.row_end && n < g.N)
-          *reinterpret_cast<u32x2*>(C + (size_t)m * g.ldc + n) =
-              u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+        for (int x = 0; x < 4; ++x) sum[x] += v[x];
       }
+      const int m = tile.row0 + wm * (TM * 16) + i * 16 + (lane & 15);
+      const int n = col0 + wn * (TNH * 16) + (jj % TNH) * 16 + 4 * (lane >> 4);
+      if (m < tile.row_end && n < g.N)
+        *reinterpret_cast<u32x2*>(C + (size_t)m * g.ldc + n) =
+            u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+    }
   }
 
   static __device__ void run(const MArgs& g, char* smem) {
@@ -893,7 +893,7 @@ int launch(MArgs g, hipStream_t s) {
   if constexpr (G::SPLIT) {
     if (g.partial) {
       mfma_split_finish_kernel<BM, BN, BK, WM, WN, NSA, NSB, MODE, TAIL>
-          <<<g.cus / 2 + G::kIdHoles, G::NT, 0, s>>>(g);
+          <<<(g.cus / 2 + G::kIdHoles) * G::TM, G::NT, 0, s>>>(g);
       BTX_LAUNCH_CHECK();
     }
   }
@@ -908,9 +908,9 @@ bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh
 
 constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
 
-// fp32 accumulators of the K slices of DOWN / BWD_DX's last round: at most cus + 8 * 4 (tile, slice) pairs
+// fp32 accumulators of the K slices of DOWN / BWD_DX's last round: at most cus + 8 * 8 (tile, slice) pairs
 // of 256 x 256 floats
-size_t mfma_split_bytes() { return (size_t)(kSplitMaxCus + 32) * 256 * 256 * sizeof(float); }
+size_t mfma_split_bytes() { return (size_t)(kSplitMaxCus + 8 * kSplitMaxSlices) * 256 * 256 * sizeof(float); }
 
 int mfma_prepare() {
   int rc = BTX_OK;
