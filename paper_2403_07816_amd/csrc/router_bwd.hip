@@ -221,6 +221,71 @@ __global__ __launch_bounds__(256) void dx_finish_kernel(const XT* __restrict__ d
   }
 }
 
+// The same for 9 to 32 experts, where the slice of W_router no longer fits the registers and reloading it
+// per 4 tokens (from the caches) cost 110 of the kernel's 337 us at 32 experts: the 8 wavefronts of a
+// workgroup share one slice of kDxCols columns, staged once in LDS ([expert][half][lane] 16-byte
+// pieces, so that consecutive lanes read consecutive pieces), and split the workgroup's tokens, 4 in
+// flight per wavefront.
+constexpr int kDxCols = kWave * 8;                      // columns of a workgroup: 8 per lane
+constexpr int kDxWaves = 8;
+constexpr int kDxLdsMaxE = 32;                          // 32 experts x 512 columns x 4 bytes = 64 KB
+template <typename XT>
+__global__ __launch_bounds__(kDxWaves* kWave) void dx_finish_lds_kernel(const XT* __restrict__ dxs,
+                                                                        const int32_t* __restrict__ inv_pos,
+                                                                        const float* __restrict__ ds,
+                                                                        const float* __restrict__ WrT, int T, int d, int E,
+                                                                        int k, int tok_per_block, XT* __restrict__ dX) {
+  extern __shared__ f32x4 s_wr[];                       // [E][2][kWave]
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int cb = blockIdx.y * kDxCols, c0 = cb + lane * 8;
+  for (int i = threadIdx.x; i < E * (kDxCols / 4); i += kDxWaves * kWave) {
+    const int e = i / (kDxCols / 4), c4 = i % (kDxCols / 4);      // 16-byte piece c4 of expert e's slice
+    f32x4 w{0.f, 0.f, 0.f, 0.f};
+    if (cb + 4 * c4 < d) w = *reinterpret_cast<const f32x4*>(WrT + (size_t)e * d + cb + 4 * c4);
+    s_wr[(e * 2 + (c4 & 1)) * kWave + (c4 >> 1)] = w;
+  }
+  __syncthreads();
+  if (c0 >= d) return;                      // no barrier and no cross-lane traffic below
+  const int t_end = min(T, (int)(blockIdx.x + 1) * tok_per_block);
+  for (int t0 = blockIdx.x * tok_per_block + wave * 4; t0 < t_end; t0 += kDxWaves * 4) {
+    float acc[4][8] = {};
+    // slot by slot, the four tokens' rows in flight together; a dropped pair (or a token past
+    // the end) reads row 0 and adds zero
+#pragma unroll 2
+    for (int j = 0; j < k; ++j) {
+      float v[4][8];
+      bool have[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int t = t0 + q;
+        const int r = t < t_end ? inv_pos[(size_t)t * k + j] : -1;
+        have[q] = r >= 0;
+        RowVec<XT, 8>::ld_stream(dxs + (size_t)max(r, 0) * d + c0, v[q]);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[q][i] += have[q] ? v[q][i] : 0.f;
+    }
+    for (int e = 0; e < E; ++e) {
+      const f32x4 wa = s_wr[(e * 2) * kWave + lane], wb = s_wr[(e * 2 + 1) * kWave + lane];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float w = ds[(size_t)min(t0 + q, T - 1) * E + e];   // uniform across the wavefront
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[q][i] = fmaf(w, wa[i], acc[q][i]);
+          acc[q][4 + i] = fmaf(w, wb[i], acc[q][4 + i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (t0 + q < t_end) RowVec<XT, 8>::st_stream(dX + (size_t)(t0 + q) * d + c0, acc[q]);
+  }
+}
+
 }  // namespace
 
 // token chunk of the dW_router partial sums: longer chunks for many experts keep the partials
@@ -279,7 +344,12 @@ int launch_router_bwd(const RouterBwdArgs& a, hipStream_t s) {
                                                                                                       a.E, a.k, dX)
     if (a.E <= 4) BTX_DX_LAUNCH(4, 16);
     else if (a.E <= 8) BTX_DX_LAUNCH(8, 16);
-    else BTX_DX_LAUNCH(16, 32);
+    else if (a.E <= kDxLdsMaxE) {
+      const int tok = 128;                              // tokens per workgroup: the slice is staged once for them
+      dx_finish_lds_kernel<XT><<<dim3(ceil_div(a.T, tok), ceil_div(a.d, kDxCols)), kDxWaves * kWave,
+                                 (size_t)a.E * kDxCols * sizeof(float), s>>>(dxs, a.inv_pos, ds, WrT, a.T, a.d, a.E, a.k,
+                                                                              tok, dX);
+    } else BTX_DX_LAUNCH(16, 32);
 #undef BTX_DX_LAUNCH
   };
   if (a.dtype == BTX_BF16) dx_launch(bf16_t{});
