@@ -30,7 +30,10 @@ def test_config0_shape_fp32_forward_backward():
                                        (1000, 128, 64, 64, 4), (17, 8, 8, 1, 1),
                                        # expert counts that leave the last register chunk of the router kernels
                                        # partly empty (8 per pass forward, 16 in the backward)
-                                       (45, 64, 64, 33, 5), (300, 128, 96, 17, 3), (257, 72, 40, 9, 9)])
+                                       (45, 64, 64, 33, 5), (300, 128, 96, 17, 3), (257, 72, 40, 9, 9),
+                                       # more than 8 experts: router logits from the matrix cores, 16 experts per
+                                       # set (3 sets here), rows that end inside a 32-column piece
+                                       (2000, 200, 64, 48, 6)])
 def test_ragged_shapes_fp32(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, F32)
 
