@@ -612,10 +612,11 @@ struct Gemm {
     if constexpr (MODE == BWD_ACT) {
       constexpr int ROWB = TNH * 32;                  // bytes per band row
       constexpr int CPR = ROWB / 16, RPI = 64 / CPR, NI = 32 / RPI;
-      static_assert(3 * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
-      char* bufA = smem + wave * (3 * 32 * ROWB);
+      static_assert(5 * 32 * ROWB * NW <= LDS_BYTES, "epilogue bands must fit the operand stages");
+      char* bufA = smem + wave * (5 * 32 * ROWB);
       char* bufB = bufA + 32 * ROWB;
       char* bufC = bufB + 32 * ROWB;
+      char* bufT = bufC + 32 * ROWB;                  // two bands of g * act, transposed: [column][64 rows]
       const int cr = lane / CPR, cc = lane % CPR;     // row (per pass) and chunk of the row-contiguous view
       const int cn = wcol0 + cc * 8;
       u32x4 p1[NI], p3[NI];
@@ -693,41 +694,44 @@ struct Gemm {
           // A pair of transposing reads turns 16 columns x 8 rows per 16-lane group around: lane
           // 4a+b of a group receives element b of what lanes a, a+4, a+8, a+12 fetched, so lane r
           // fetches band row 8*group + r/4 (then +4) at columns 4*(r%4).. and ends up with rows
-          // 8*group .. +7 of column r: 16 contiguous bytes of the transposed matrix.  Those go
-          // back into the same buffer as [column][32 rows] (64 bytes per column, chunks swizzled
-          // by column) and are read so that four consecutive lanes hold one column's 64 bytes:
-          // scattered 16-byte stores cost the address unit four times as much.  Rows past the
-          // group's end are zeros (see the gate above) and are written up to the 64-row padding.
+          // 8*group .. +7 of column r: 16 contiguous bytes of the transposed matrix.  Those are
+          // collected over two bands as [column][64 rows] (128 bytes per column, chunks swizzled by
+          // column) and read back so that eight consecutive lanes hold one column's 128 bytes: whole,
+          // aligned cache lines per store (with 64-byte pieces, one band at a time, these stores moved
+          // 3.1 TB/s where the row stores of dh1/dh3 move 5.1; scattered 16-byte stores cost the address
+          // unit four times as much again).  Rows past the group's end are zeros (see the gate above) and
+          // are written up to the 64-row padding.
           typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+          static_assert(NB % 2 == 0, "bands are turned around in pairs");
           const int o_e = tile.exp_row0;
           const int pad_e = (row_end - o_e + 63) & ~63;
           const int fr = 8 * lane_c + (lane_m >> 2), fa4 = lane_m & 3;
-          const int qc = lane >> 2, qg = lane & 3;        // read-back view: column within 16, 8-row chunk
-          const int m8 = mb + 8 * qg - o_e;              // grouped row of that chunk, relative to the expert
-          auto turn = [&](char* buf, bf16_t* T) {
-            bf16x8 v[TNH];
+          bf16x8 v[TNH];
 #pragma unroll
-            for (int pr = 0; pr < TNH; ++pr) {
-              const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
-              const uint32_t o_hi = stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
-              const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_lo));
-              const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(buf + o_hi));
-              v[pr] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
+          for (int pr = 0; pr < TNH; ++pr) {
+            const uint32_t o_lo = stage_off<ROWB, 8>(fr, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+            const uint32_t o_hi = stage_off<ROWB, 8>(fr + 4, 2 * pr + (fa4 >> 1)) + 8 * (fa4 & 1);
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(bufC + o_lo));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(bufC + o_hi));
+            v[pr] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          }
 #pragma unroll
-            for (int pr = 0; pr < TNH; ++pr) {
-              const int tc = 16 * pr + lane_m;
-              *reinterpret_cast<bf16x8*>(buf + tc * 64 + ((lane_c ^ ((tc >> 2) & 3)) << 4)) = v[pr];
-            }
+          for (int pr = 0; pr < TNH; ++pr) {
+            const int tc = 16 * pr + lane_m;             // column; chunk = 8 rows: 4 per band
+            *reinterpret_cast<bf16x8*>(bufT + tc * 128 + ((((ib & 1) * 4 + lane_c) ^ ((tc >> 1) & 7)) << 4)) = v[pr];
+          }
+          if (ib & 1) {
+            const int qc = lane >> 3, qg = lane & 7;     // read-back view: column within 8, 8-row chunk of the pair
+            const int m8 = mb - 32 + 8 * qg - o_e;       // grouped row of that chunk, relative to the expert
 #pragma unroll
-            for (int pr = 0; pr < TNH; ++pr) {
-              const int tc = 16 * pr + qc;
-              const bf16x8 w = *reinterpret_cast<const bf16x8*>(buf + tc * 64 + ((qg ^ ((tc >> 2) & 3)) << 4));
+            for (int pr = 0; pr < 2 * TNH; ++pr) {
+              const int tc = 8 * pr + qc;
+              const bf16x8 w = *reinterpret_cast<const bf16x8*>(bufT + tc * 128 + ((qg ^ ((tc >> 1) & 7)) << 4));
               const int col = wcol0 + tc;
-              if (col < g.N && m8 < pad_e) store_out<STREAM_OUT>(reinterpret_cast<bf16x8*>(T + (size_t)col * g.ldt + kp_begin + m8), w);
+              if (col < g.N && m8 < pad_e)
+                store_out<STREAM_OUT>(reinterpret_cast<bf16x8*>(g.T2 + (size_t)col * g.ldt + kp_begin + m8), w);
             }
-          };
-          turn(bufC, g.T2);
+          }
         }
       }
     } else {
