@@ -917,6 +917,7 @@ constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one
 size_t mfma_split_bytes() { return (size_t)(kSplitMaxCus + 8 * kSplitMaxSlices) * 256 * 256 * sizeof(float); }
 
 int mfma_prepare() {
+  if (compute_units() <= 0) return BTX_ERR_HIP;        // looked up once per device, here rather than in a launch
   int rc = BTX_OK;
   auto both = [&](auto mode_tag, auto bn_tag) {
     constexpr int MODE = decltype(mode_tag)::value, BN = decltype(bn_tag)::value;
