@@ -46,6 +46,14 @@ def test_top1_variants_with_biased_router_fp32(mode, lb_mode, flags):
                         alpha=0.5)
 
 
+@pytest.mark.parametrize("mode", [B.BTX_ROUTE_SWITCH_TOP1, B.BTX_ROUTE_SAMPLE_TOP1, B.BTX_ROUTE_GUMBEL_TOP1])
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_top1_variants_with_many_experts(mode, dtype):
+    """The top-1 selections on logits that come from the matrix cores (more than 8 experts)."""
+    bias = [1.5, 0, 0, -0.5, 0, 0, 0.5, 0, 0, 0, 0, 0]
+    run_layer_and_check(500, 160, 96, 12, 1, dtype, mode=mode, bias=bias, unit_rms=(dtype == BF16), tau=0.7)
+
+
 @pytest.mark.parametrize("lb_mode,flags,lam", [(B.BTX_LB_TOKEN_FRAC, 0, 1.0), (B.BTX_LB_GATE_MEAN, 0, 1.0),
                                                (B.BTX_LB_GATE_MEAN, B.BTX_FLAG_LB_GRAD_THROUGH_U, 2.0),
                                                (B.BTX_LB_TOKEN_FRAC, 0, 0.0)])
