@@ -27,7 +27,10 @@
 //   * grouped rows: tiles are enumerated per expert on the device (no host sync); a tile past
 //     the last one exits.  Rows beyond a group's end are loaded from a clamped address and
 //     never stored.  A last k tile that is half empty (K = 32 mod 64) has its copies re-pointed
-//     at valid data and the A fragments of its empty half zeroed in registers.
+//     at valid data and the A fragments of its empty half zeroed in registers;
+//   * DOWN and BWD_DX (16 column tiles of many k tiles each): the tiles of a partly filled last round
+//     of workgroups are cut along K into up to 8 slices whose fp32 accumulators a second small kernel
+//     adds in ascending order (Gemm::split_plan), so that the round fills the chip.
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
 #include <type_traits>
