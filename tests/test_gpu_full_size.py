@@ -190,6 +190,14 @@ def test_config2_forward_backward_T16384_as_benchmarked(big):
         assert torch.equal(a, b)
 
 
+def test_soft_routing_every_expert_T4096(big):
+    """Soft routing (Sec. 3.3): k = E, every token goes through all four full-width experts
+    (16384 routed rows in four equal groups), one 4096-token sequence, forward and backward."""
+    r, out, g, fwd = run_full(big, 4096, 4, B.BTX_ROUTE_TOPK_RENORM, 0.01, 1.0, big["W1"], big["W3"], big["W2"],
+                              big["W_router"], what="soft routing k=E=4, T=4096")
+    assert [int(c) for c in r.counts.tolist()] == [4096] * 4
+
+
 def test_config3_gumbel_sample_top1(big):
     """Sample top-1 as printed (Gumbel-softmax soft sample, largest entry kept), temperature 0.5."""
     g = torch.Generator(device="cuda")
