@@ -26,9 +26,9 @@
  *   - T == 0 is a valid no-op (BTX_OK).
  *   - Every kernel is free of atomics: results are bit-identical run to run.  The order
  *     of every sum is fixed by the shapes, the routing counts and the number of compute
- *     units of the device (the bf16 down-projection and input-gradient products cut the
- *     tiles of a partly filled last round of workgroups into up to eight K ranges, added in
- *     ascending order by a second kernel).
+ *     units of the device (the bf16 up-projection, down-projection and input-gradient
+ *     products cut the tiles of a partly filled last round of workgroups into up to eight K
+ *     ranges, added in ascending order by a second kernel).
  *   - Outputs must not alias inputs unless stated.  NaN/Inf inputs give
  *     unspecified results.
  */

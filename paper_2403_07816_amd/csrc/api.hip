@@ -268,7 +268,7 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   const bool fused = ff_gather_fused(dtype, T, d, f);
   if (!fused) BTX_STAGE(BTX_STAGE_GATHER_X, launch_gather_rows(x, w.xs, perm, R, k, d, dtype, s));
   const RowSource xs = fused ? RowSource{x, perm, k} : RowSource{w.xs, nullptr, 1};
-  BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, w.act, nullptr, s));
+  BTX_STAGE(BTX_STAGE_UP, launch_up_swiglu(dtype, xs, W1, W3, offsets, sh, h1, h3, w.act, w.partial, s));
   BTX_STAGE(BTX_STAGE_DOWN, launch_down(dtype, w.act, W2, offsets, sh, w.y, w.partial, s));
   BTX_STAGE(BTX_STAGE_COMBINE, launch_combine(w.y, gates, inv_pos, residual, out, T, k, d, dtype, s));
   return BTX_OK;

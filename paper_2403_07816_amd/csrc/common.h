@@ -248,11 +248,12 @@ bool ff_gather_fused(int dtype, int T, int d, int f);
 // ff_up_needs_h() is false: the plain path computes act from the stored h1/h3.
 bool ff_up_needs_h(int dtype, int d, int f);
 int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
-                     const FfShapes& sh, void* h1, void* h3, void* act, void* scratch, hipStream_t s);
-// y = act W2
-// partial: ff_split_bytes() of scratch (the bf16 MFMA path cuts the tiles of a partly filled last round along K
-// and adds the slices in a second kernel); may be NULL when ff_split_bytes() is 0
+                     const FfShapes& sh, void* h1, void* h3, void* act, void* partial, hipStream_t s);
+// partial (here, in launch_down and in launch_bwd_dx): ff_split_bytes() of scratch (the bf16 MFMA path cuts the
+// tiles of a partly filled last round along K and adds the slices in a second kernel); may be NULL when
+// ff_split_bytes() is 0.  Products that follow each other on a stream may share it.
 size_t ff_split_bytes(int dtype, int d, int f);
+// y = act W2
 int launch_down(int dtype, const void* act, const void* W2, const int32_t* offsets, const FfShapes& sh, void* y,
                 void* partial, hipStream_t s);
 // D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a.

@@ -32,8 +32,8 @@ bool ff_up_needs_h(int dtype, int d, int f) { return !(dtype == BTX_BF16 && mfma
 int bwd_act_partials(int dtype, int f) { return dtype == BTX_BF16 ? mfma_bwd_act_partials(f) : 1; }
 
 int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
-                     const FfShapes& sh, void* h1, void* h3, void* act, void* /*scratch*/, hipStream_t s) {
-  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_up_swiglu(xs, W1, W3, offsets, sh, h1, h3, act, s);
+                     const FfShapes& sh, void* h1, void* h3, void* act, void* partial, hipStream_t s) {
+  if (dtype == BTX_BF16 && mfma_shape(sh.d, sh.f)) return mfma_up_swiglu(xs, W1, W3, offsets, sh, h1, h3, act, partial, s);
   if (xs.perm) return BTX_ERR_UNSUPPORTED;  // the plain path takes gathered rows
   return generic_up_swiglu(dtype, xs.base, W1, W3, offsets, sh, h1, h3, act, s);
 }

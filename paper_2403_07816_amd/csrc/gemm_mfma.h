@@ -11,7 +11,7 @@ int mfma_bwd_act_partials(int f);
 // gathered A rows need every byte offset inside the source to fit 32 bits
 bool mfma_gather_ok(int T, int d);
 int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
-                   void* h1, void* h3, void* act, hipStream_t s);
+                   void* h1, void* h3, void* act, void* partial, hipStream_t s);
 // partial: mfma_split_bytes() of scratch for the K slices of the last round (NULL: tiles are never cut)
 size_t mfma_split_bytes();
 int mfma_down(const void* act, const void* W2, const int32_t* off, const FfShapes& sh, void* y, void* partial,

@@ -28,9 +28,9 @@
 //     the last one exits.  Rows beyond a group's end are loaded from a clamped address and
 //     never stored.  A last k tile that is half empty (K = 32 mod 64) has its copies re-pointed
 //     at valid data and the A fragments of its empty half zeroed in registers;
-//   * DOWN and BWD_DX (16 column tiles of many k tiles each): the tiles of a partly filled last round
-//     of workgroups are cut along K into up to 8 slices whose fp32 accumulators a second small kernel
-//     adds in ascending order (Gemm::split_plan), so that the round fills the chip.
+//   * UP, DOWN and BWD_DX: the tiles of a partly filled last round of workgroups are cut along K into
+//     up to 8 slices whose fp32 accumulators a second small kernel adds in ascending order and stores
+//     (UP: with the SwiGLU applied to the sums), so that the round fills the chip (Gemm::split_plan).
 #include "gemm_mfma.h"
 #include "gemm_generic.h"
 #include <type_traits>
@@ -64,7 +64,7 @@ struct MArgs {
   int c_is_f32;
   int blocks_per_e;                     // grouped-K: block ids per expert (a multiple of 8)
   int total_ids;                        // tile ids of the launch (a few name no tile: padding of the id space)
-  // DOWN / BWD_DX: the tiles of the last, partly filled round are cut along K (see Gemm::split_plan)
+  // UP / DOWN / BWD_DX: the tiles of the last, partly filled round are cut along K (see Gemm::split_plan)
   f32x4* partial; int cus;              // fp32 accumulators of the slices (NULL: never cut); compute units
 };
 
@@ -297,12 +297,13 @@ struct Gemm {
 
   // DOWN and BWD_DX have few, long tiles (16 column tiles): their last round is often a small fraction of
   // the chip (8.25 rounds for the benchmark's top-2 layer, 4.1 for top-1, 2.25 for one sequence), and a
-  // tile cannot be cut smaller.  So the tiles of that round are cut along K instead: slice s of a
+  // tile cannot be cut smaller; UP has 44.3, 22.2 and 11.4 rounds there.  So the tiles of that round are cut
+  // along K instead: slice s of a
   // left-over tile runs k tiles [s nk/S, (s+1) nk/S) in a workgroup of its own and leaves its fp32
   // accumulators in `partial`; a second, small kernel adds the S slices of a tile in slice order and stores
   // the result.  No atomics, and the order of every sum is fixed by the shapes and the number of compute
   // units alone.  ids >= total_ids are the workgroups of the slices 1 .. S-1.
-  static constexpr bool SPLIT = (MODE == DOWN || MODE == BWD_DX);
+  static constexpr bool SPLIT = (MODE == DOWN || MODE == BWD_DX || MODE == UP);
   static constexpr int kMaxSlices = kSplitMaxSlices, kMinSliceTiles = 16, kIdHoles = 8;   // the id space has up to 8 ids past the last tile
   struct SplitPlan { int id_full, n_left, n_slices; };
   static __device__ __forceinline__ SplitPlan split_plan(const MArgs& g, int n_rt) {
@@ -339,9 +340,7 @@ struct Gemm {
     Tile tile;
     if (!locate(g, experts, plan.id_full + j, tile)) return;
     const int col0 = tile.tile_n * BNH;
-    bf16_t* C = static_cast<bf16_t*>(g.C0);
-#pragma unroll
-    for (int jj = 0; jj < TN; ++jj) {
+    auto slices_sum = [&](int jj) {
       const size_t at = (size_t)wave * (TM * TN * kWave) + (i * TN + jj) * kWave + lane;
       f32x4 sum = __builtin_nontemporal_load(partial_slot(g, plan, j, 0) + at);
       for (int sl = 1; sl < plan.n_slices; ++sl) {
@@ -349,11 +348,30 @@ struct Gemm {
 #pragma unroll
         for (int x = 0; x < 4; ++x) sum[x] += v[x];
       }
-      const int m = tile.row0 + wm * (TM * 16) + i * 16 + (lane & 15);
-      const int n = col0 + wn * (TNH * 16) + (jj % TNH) * 16 + 4 * (lane >> 4);
-      if (m < tile.row_end && n < g.N)
-        *reinterpret_cast<u32x2*>(C + (size_t)m * g.ldc + n) =
-            u32x2{pack_bf16x2(sum[0], sum[1]), pack_bf16x2(sum[2], sum[3])};
+      return sum;
+    };
+    auto put = [&](void* C, size_t idx, const f32x4& v) {
+      *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(C) + idx) = u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+    };
+    const int m = tile.row0 + wm * (TM * 16) + i * 16 + (lane & 15);
+#pragma unroll
+    for (int jj = 0; jj < TNH; ++jj) {
+      const int n = col0 + wn * (TNH * 16) + jj * 16 + 4 * (lane >> 4);
+      const bool inside = m < tile.row_end && n < g.N;
+      const size_t idx = (size_t)m * g.ldc + n;
+      if constexpr (MODE == UP) {                        // fragment jj holds x W1, fragment jj + TNH x W3 of the same outputs
+        const f32x4 h1 = slices_sum(jj), h3 = slices_sum(jj + TNH);
+        f32x4 a;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) a[x] = silu_f(h1[x]) * h3[x];
+        if (inside) {
+          if (g.C0) { put(g.C0, idx, h1); put(g.C1, idx, h3); }
+          put(g.C2, idx, a);
+        }
+      } else {
+        const f32x4 sum = slices_sum(jj);
+        if (inside) put(g.C0, idx, sum);
+      }
     }
   }
 
@@ -915,7 +933,7 @@ bool fast_ok(const FfShapes& sh) { return sh.d % 32 == 0 && sh.f % 32 == 0 && sh
 
 constexpr int kActBN = 256;  // column tile of the BWD_ACT kernel = width of one dg partial
 
-// fp32 accumulators of the K slices of DOWN / BWD_DX's last round: at most cus + 8 * 8 (tile, slice) pairs
+// fp32 accumulators of the K slices of the last round of UP / DOWN / BWD_DX: at most cus + 8 * 8 (tile, slice) pairs
 // of 256 x 256 floats
 size_t mfma_split_bytes() { return (size_t)(kSplitMaxCus + 8 * kSplitMaxSlices) * 256 * 256 * sizeof(float); }
 
@@ -941,10 +959,10 @@ int mfma_bwd_act_partials(int f) { return ceil_div(f, kActBN); }
 bool mfma_gather_ok(int T, int d) { return (int64_t)T * d * 2 < ((int64_t)1 << 32); }
 
 int mfma_up_swiglu(const RowSource& xs, const void* W1, const void* W3, const int32_t* off, const FfShapes& sh,
-                   void* h1, void* h3, void* act, hipStream_t s) {
+                   void* h1, void* h3, void* act, void* partial, hipStream_t s) {
   if (!fast_ok(sh)) return BTX_ERR_UNSUPPORTED;
   MArgs g{};
-  g.A0 = (const bf16_t*)xs.base; g.a_perm = xs.perm; g.a_k = xs.k; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act;
+  g.A0 = (const bf16_t*)xs.base; g.a_perm = xs.perm; g.a_k = xs.k; g.B0 = (const bf16_t*)W1; g.B1 = (const bf16_t*)W3; g.C0 = h1; g.C1 = h3; g.C2 = act; g.partial = (f32x4*)partial;
   g.offsets = off; g.E = sh.E; g.N = sh.f; g.K = sh.d; g.lda = sh.d; g.ldb = sh.f; g.ldc = sh.f;
   g.strideB_e = sh.s13; g.R = sh.R;
   return sh.d % 64 ? launch<256, 256, 64, 2, 4, 3, 2, UP, true>(g, s) : launch<256, 256, 64, 2, 4, 3, 2, UP>(g, s);
