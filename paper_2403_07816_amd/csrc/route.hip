@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_tokens_kernel(
   constexpr int G = MATRIX ? MG : 1;
   __shared__ float s_logit[kWavesPerBlock][kTokPerWave][kMaxExperts];
   __shared__ float s_stat[kWavesPerBlock][3][kMaxExperts];
-  extern __shared__ float s_part[];                     // MATRIX: [wavefront][G * kTokPerBlock tokens][16 n_sets]
+  extern __shared__ float s_part[];                     // MATRIX: [wavefront][G * kTokPerBlock tokens][16 NS experts]
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int n_blk = (T + kTokPerBlock - 1) / kTokPerBlock;
