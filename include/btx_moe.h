@@ -130,7 +130,9 @@ int btx_profile_stages(void** events, int n_pairs);
  *   tau                temperature of GUMBEL_TOP1 (> 0); ignored by the other modes
  *   capacity_factor    0 = dropless.  > 0: every expert keeps its first
  *                      ceil(capacity_factor * T*k / E) pairs in (t,j) order (Sec. 4.3: "a hard
- *                      limit after which routed tokens will be dropped"); a dropped pair gets
+ *                      limit after which routed tokens will be dropped"; the product is taken in
+ *                      double precision on the float passed, so 0.8f, which lies above 0.8,
+ *                      gives 209 and not 208 at T*k/E = 260); a dropped pair gets
  *                      inv_pos = -1, no grouped row and contributes nothing to the layer's output
  *                      or to dg; counts, gate_sum and lb_loss describe the routing before drops,
  *                      offsets the kept rows; perm[r] = 0 for r >= offsets[E]

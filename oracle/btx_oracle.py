@@ -340,6 +340,7 @@ def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: 
             dW1[e] = xe.T @ dh1
             dW3[e] = xe.T @ dh3
 
+    dg_ff = dg                                   # <dY_t, FF_e(x_t)> alone, reported beside the total
     if grad_through_u:
         # u_i = mean_t g_ti, so L_LB also depends on every gate: dL/dg_ti = alpha*N*p_i/T
         assert lb_mode == LB_GATE_MEAN
@@ -371,7 +372,7 @@ def moe_backward(x, W_router, b_router, W1, W3, W2, k: int, mode: int, dY, fwd: 
         ds += lb_grad_scale * lb_grad_logits(probs, u, alpha, T_batch)
 
     dX += ds @ Wr.T
-    return {"dX": dX, "dW_router": x.T @ ds, "db_router": ds.sum(axis=0), "ds": ds, "dg": dg,
+    return {"dX": dX, "dW_router": x.T @ ds, "db_router": ds.sum(axis=0), "ds": ds, "dg": dg, "dg_ff": dg_ff,
             "dW1": dW1, "dW3": dW3, "dW2": dW2}
 
 

@@ -56,7 +56,7 @@ BwdWs carve_backward(void* ws, int T, int d, int f, int E, int k, int dtype) {
   // transposed path: dW2 reads ga as [f][padded rows]
   w.ga = c.take(tr ? (size_t)f * ff_dw_pitch((int)R, E) * es : R * f * es);
   w.dxs = c.take(R * d * es);
-  w.dg_part = static_cast<float*>(c.take(R * (size_t)bwd_act_partials(dtype, f) * sizeof(float)));
+  w.dg_part = static_cast<float*>(c.take(R * (size_t)bwd_act_partials(dtype, d, f) * sizeof(float)));
   w.scratch = c.take(ff_scratch_bytes(dtype, (int)R, f));
   w.router = c.take(router_bwd_workspace_bytes(T, d, E));
   const size_t split = ff_split_bytes(dtype, d, f);      // K slices of BWD_DX's last round
@@ -329,7 +329,7 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
     BTX_STAGE(BTX_STAGE_DW2, launch_bwd_dw2(dtype, dW_dtype, w.ga, tr ? w.dysT : w.dys, offsets, sh, dW2, s));
   }
   RouterBwdArgs ra{x, dtype, W_router, T, d, E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, noise, tau,
-                   topk_idx, gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, f), w.dxs, dX,
+                   topk_idx, gates, probs, inv_pos, gate_sum, prob_sum, counts, w.dg_part, bwd_act_partials(dtype, d, f), w.dxs, dX,
                    dW_router, db_router, w.router};
   BTX_STAGE(BTX_STAGE_ROUTER_BWD, launch_router_bwd(ra, s));
   return BTX_OK;

@@ -259,7 +259,9 @@ int launch_down(int dtype, const void* act, const void* W2, const int32_t* offse
 // D = dys W2^T; dg_part[r,p] partial sums of D*a; da = g*D; dh1 = da*h3*silu'(h1); dh3 = da*silu(h1); ga = g*a.
 // dh1, dh3: [R,f].  When ff_dw_transposed() holds, `ga` receives g*a transposed and padded
 // ([f][ff_dw_pitch()]), or nothing at all when want_dw is false; otherwise ga is [R,f].
-int bwd_act_partials(int dtype, int f);
+// bwd_act_partials: partial sums per grouped row that launch_bwd_act writes for these shapes (one per 256-column
+// tile on the bf16 MFMA path, a single sum otherwise)
+int bwd_act_partials(int dtype, int d, int f);
 int launch_bwd_act(int dtype, const RowSource& dys, const void* W2, const void* h1, const void* h3, const float* gates,
                    const int32_t* perm, const int32_t* offsets, const FfShapes& sh, void* dh1, void* dh3, void* ga,
                    bool want_dw, float* dg_part, void* scratch, hipStream_t s);

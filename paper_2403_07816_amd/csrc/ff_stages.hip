@@ -29,7 +29,7 @@ bool ff_gather_fused(int dtype, int T, int d, int f) {
 
 bool ff_up_needs_h(int dtype, int d, int f) { return !(dtype == BTX_BF16 && mfma_shape(d, f)); }
 
-int bwd_act_partials(int dtype, int f) { return dtype == BTX_BF16 ? mfma_bwd_act_partials(f) : 1; }
+int bwd_act_partials(int dtype, int d, int f) { return dtype == BTX_BF16 && mfma_shape(d, f) ? mfma_bwd_act_partials(f) : 1; }
 
 int launch_up_swiglu(int dtype, const RowSource& xs, const void* W1, const void* W3, const int32_t* offsets,
                      const FfShapes& sh, void* h1, void* h3, void* act, void* partial, hipStream_t s) {

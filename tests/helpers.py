@@ -56,6 +56,13 @@ def reconcile_routing(idx_gpu: np.ndarray, orc: dict, mode: int, U):
     return forced, len(diff)
 
 
+def as_passed(v):
+    """The value a C `float` argument of the library receives for the Python number v: the oracle is
+    given the same number (ceil(capacity_factor * T*k / E) differs between 0.8 and float32(0.8) at
+    T*k/E = 260)."""
+    return float(np.float32(v))
+
+
 def run_oracle_forward(L, k, mode, alpha, lb_mode, forced=None, keep_y=False, tau=1.0, cf=0.0):
     return O.moe_forward(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
                          experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["U"]), alpha, lb_mode,
@@ -136,12 +143,14 @@ def bf16_storage_model_dg(x, dY, W1, W3, W2, fwd):
     return dg
 
 
-def router_grads_from_dg(x, dg, fwd, ref, mode, tau=1.0):
-    """dW_router and db_router that follow from a given dg: the oracle's d(logits) with its own dg
-    taken out and the given one put in (the gate Jacobians are linear in dg)."""
+def router_grads_from_dg(x, dg, fwd, ref, mode, tau=1.0, with_ds=False):
+    """dW_router and db_router that follow from a given dg = <dY, expert output>: the oracle's
+    d(logits) with its own such dg taken out and the given one put in (the gate Jacobians are linear
+    in dg; what the load-balancing loss adds to dg stays as it is).  with_ds: also the d(logits) they
+    are the sums of."""
     g, idx = fwd["gates"], fwd["idx"]
     T, E = fwd["probs"].shape
-    ddg = dg - ref["dg"]
+    ddg = dg - ref["dg_ff"]
     ds = np.array(ref["ds"], dtype=np.float64)
     if mode == B.BTX_ROUTE_TOPK_RENORM:
         sel = g * (ddg - np.sum(g * ddg, axis=1, keepdims=True))
@@ -153,10 +162,27 @@ def router_grads_from_dg(x, dg, fwd, ref, mode, tau=1.0):
         np.add.at(row, (np.arange(T), idx[:, 0]), ye[:, 0])
         ds = ds + ddg * row / (tau if mode == B.BTX_ROUTE_GUMBEL_TOP1 else 1.0)
     x = np.asarray(x, np.float64)
+    if with_ds:
+        return x.T @ ds, ds.sum(axis=0), ds
     return x.T @ ds, ds.sum(axis=0)
 
 
+def sum_condition(x, ds):
+    """How far the two router gradients cancel as sums over the tokens: the norm of the sums of the
+    terms' magnitudes over the norm of the sums, for dW_router = sum_t x_t^T ds_t and db_router =
+    sum_t ds_t.  A perturbation that is small next to the terms is that many times larger next to
+    the sum."""
+    x, ds = np.asarray(x, np.float64), np.asarray(ds, np.float64)
+
+    def ratio(magnitudes, total):
+        n = np.linalg.norm(total)
+        return float(np.linalg.norm(magnitudes) / n) if n > 0 else float("inf")
+    return {"dW_router": ratio(np.abs(x).T @ np.abs(ds), x.T @ ds),
+            "db_router": ratio(np.abs(ds).sum(axis=0), ds.sum(axis=0))}
+
+
 MODEL_TOL = 2e-3     # the library's router gradients against the bf16 storage model (observed: at most 5e-4)
+MODEL_COND = 20.0    # ... for sums that cancel no further than this (the named workloads: 10 to 17)
 
 
 def check_router_grads_bf16(g, L, fwd, ref, mode, tau=1.0, what=""):
@@ -167,7 +193,11 @@ def check_router_grads_bf16(g, L, fwd, ref, mode, tau=1.0, what=""):
     are independent between experts) do not.  Two assertions:
       * against bf16_storage_model_dg, i.e. the exact gradient of a layer whose h1, h3 were rounded
         to bf16 and nothing else: within MODEL_TOL.  Whatever the library's own arithmetic adds to
-        the unavoidable storage error is bounded by this, a tenth of the bar;
+        the unavoidable storage error is bounded by this, a tenth of the bar.  The library's fp32
+        sums perturb every token's d(logits) a little; how large that is next to a gradient grows
+        with the cancellation of the gradient's sum over the tokens (sum_condition: 10 to 17 on the
+        named workloads, 190 for db_router when every token goes to all three of three experts), so
+        beyond MODEL_COND the bar grows in proportion;
       * against the exact oracle: the stated 2e-2, except where the storage model itself is further
         than that from the oracle (db_router on a few hundred tokens): there the model's own error
         plus a tenth.
@@ -178,21 +208,24 @@ def check_router_grads_bf16(g, L, fwd, ref, mode, tau=1.0, what=""):
     kappa = router_condition(fwd, ref, mode)
     dg_model = bf16_storage_model_dg(to_np(L["x"]), to_np(L["dY"]), experts_np(L["W1"]), experts_np(L["W3"]),
                                      experts_np(L["W2"]), fwd)
-    dWr_m, db_m = router_grads_from_dg(to_np(L["x"]), dg_model, fwd, ref, mode, tau)
+    dWr_m, db_m, ds_m = router_grads_from_dg(to_np(L["x"]), dg_model, fwd, ref, mode, tau, with_ds=True)
+    cond = sum_condition(to_np(L["x"]), ds_m)
     got = {"dW_router": to_np(g.dW_router), "db_router": to_np(g.db_router)}
     model = {"dW_router": dWr_m, "db_router": db_m}
-    res = {"kappa": kappa, "dg_storage_model": rel_err(dg_model, ref["dg"])}
+    res = {"kappa": kappa, "dg_storage_model": rel_err(dg_model, ref["dg_ff"]), "sum_condition": cond}
     for name in ("dW_router", "db_router"):
         res[name] = rel_err(got[name], ref[name])
         res[name + "_storage_model"] = rel_err(model[name], ref[name])
         res[name + "_vs_model"] = rel_err(got[name], model[name])
-    print(f"[router grads {what}] kappa={kappa:.2f} dg storage-model fro={res['dg_storage_model'][0]:.3e} | " +
+    print(f"[router grads {what}] kappa={kappa:.2f} sum conditions {cond['dW_router']:.1f}/{cond['db_router']:.1f} "
+          f"dg storage-model fro={res['dg_storage_model'][0]:.3e} | " +
           " | ".join(f"{n}: vs oracle {res[n][0]:.3e}/{res[n][1]:.3e}, storage model vs oracle "
                      f"{res[n + '_storage_model'][0]:.3e}/{res[n + '_storage_model'][1]:.3e}, vs storage model "
                      f"{res[n + '_vs_model'][0]:.3e}/{res[n + '_vs_model'][1]:.3e}" for n in ("dW_router", "db_router")),
           flush=True)
     for name in ("dW_router", "db_router"):
-        assert_close(got[name], model[name], MODEL_TOL, f"{name} against the bf16 storage model")
+        assert_close(got[name], model[name], MODEL_TOL * max(1.0, cond[name] / MODEL_COND),
+                     f"{name} against the bf16 storage model (sum condition {cond[name]:.1f})")
         for i, kind in enumerate(("fro", "max")):
             bar = max(tol, 1.1 * res[name + "_storage_model"][i])
             assert res[name][i] <= bar, f"{name}: {kind} error {res[name][i]:.3e} against the oracle exceeds {bar:.3e}"
@@ -207,6 +240,7 @@ def run_layer_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
     poison=True hands the library workspaces, saved-activation buffers and output tensors whose
     every byte is 0xFF (NaN patterns in bf16 and fp32): nothing the layer returns may depend on
     memory that this call did not write."""
+    tau, cf = as_passed(tau), as_passed(cf)
     n_seed = E // split
     L = synth.make_layer(T, d, f * split, n_seed, dtype=dtype, seed=seed, unit_rms=unit_rms, router_E=E,
                          router_bias=bias, with_dY=backward, with_U=(mode == B.BTX_ROUTE_SAMPLE_TOP1),
@@ -279,6 +313,7 @@ def run_block_and_check(T, d, f, E, k, dtype, mode=B.BTX_ROUTE_TOPK_RENORM, lb_m
                         bias=None, eps=1e-5, seed=synth.BASE_SEED, cf=0.0):
     """The sublayer inside its block: out = h + FF_MoE(rmsnorm(h)), forward and backward, with the
     normalisation folded into the router kernel and its backward as a kernel of its own."""
+    cf = as_passed(cf)
     L = synth.make_layer(T, d, f, E, dtype=dtype, seed=seed, router_bias=bias, with_dY=True,
                          with_U=(mode == B.BTX_ROUTE_SAMPLE_TOP1), with_gumbel=(mode == B.BTX_ROUTE_GUMBEL_TOP1))
     gen = torch.Generator().manual_seed(seed + 77)

@@ -12,6 +12,7 @@ from paper_2403_07816_amd import synth
 
 from conftest import rel_err
 from helpers import (bf16_storage_model_dg, experts_np, router_condition, router_grads_from_dg, run_oracle_forward,
+                     sum_condition,
                      to_np)
 
 
@@ -32,15 +33,15 @@ def test_the_oracles_own_dg_reproduces_its_router_gradients(mode, k):
     a perturbed dg the gradients of the perturbed Jacobian product (checked against a direct evaluation)."""
     L, fwd, ref = layer(96, 64, 96, 4, k, mode, 0.1, bias=[0.5, 0.0, -0.5, 0.0])
     x = to_np(L["x"])
-    dWr, db = router_grads_from_dg(x, ref["dg"], fwd, ref, mode, tau=0.5)
+    dWr, db = router_grads_from_dg(x, ref["dg_ff"], fwd, ref, mode, tau=0.5)
     np.testing.assert_allclose(dWr, ref["dW_router"], rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(db, ref["db_router"], rtol=1e-12, atol=1e-15)
     rng = np.random.default_rng(3)
-    dg2 = ref["dg"] + 0.1 * rng.normal(size=ref["dg"].shape) * np.abs(ref["dg"]).mean()
+    dg2 = ref["dg_ff"] + 0.1 * rng.normal(size=ref["dg"].shape) * np.abs(ref["dg"]).mean()
     dWr2, db2 = router_grads_from_dg(x, dg2, fwd, ref, mode, tau=0.5)
     # direct evaluation: d(logits) of the gate Jacobian for dg2, plus the load-balancing term taken from the oracle
     T, E = fwd["probs"].shape
-    lb = ref["ds"] - _gate_jacobian(fwd, ref["dg"], mode, 0.5)
+    lb = ref["ds"] - _gate_jacobian(fwd, ref["dg_ff"], mode, 0.5)
     ds2 = _gate_jacobian(fwd, dg2, mode, 0.5) + lb
     np.testing.assert_allclose(dWr2, x.T @ ds2, rtol=1e-10, atol=1e-14)
     np.testing.assert_allclose(db2, ds2.sum(axis=0), rtol=1e-10, atol=1e-14)
@@ -70,7 +71,7 @@ def test_storage_error_of_dg_is_a_few_bf16_roundings_whatever_the_experts():
         L, fwd, ref = layer(512, 128, 192, 4, 2, O.ROUTE_TOPK_RENORM, spread)
         dg = bf16_storage_model_dg(to_np(L["x"]), to_np(L["dY"]), experts_np(L["W1"]), experts_np(L["W3"]),
                                    experts_np(L["W2"]), fwd)
-        fro, _ = rel_err(dg, ref["dg"])
+        fro, _ = rel_err(dg, ref["dg_ff"])
         assert 2.0 ** -10 < fro < 2.0 ** -8, fro      # two independent roundings of 2^-9 at most, averaged over f terms
 
 
@@ -84,10 +85,43 @@ def test_cancellation_between_similar_experts_amplifies_the_storage_error_in_the
         dg = bf16_storage_model_dg(to_np(L["x"]), to_np(L["dY"]), experts_np(L["W1"]), experts_np(L["W3"]),
                                    experts_np(L["W2"]), fwd)
         dWr, _ = router_grads_from_dg(to_np(L["x"]), dg, fwd, ref, O.ROUTE_TOPK_RENORM)
-        out[spread] = (rel_err(dg, ref["dg"])[0], rel_err(dWr, ref["dW_router"])[0],
+        out[spread] = (rel_err(dg, ref["dg_ff"])[0], rel_err(dWr, ref["dW_router"])[0],
                        router_condition(fwd, ref, O.ROUTE_TOPK_RENORM))
     e_dg, e_w, kappa = out[0.1]
     assert 3.0 * e_dg < e_w < kappa * e_dg and kappa > 8.0
     assert e_w < 2e-2                                  # at this workload's 10 % spread the plain bar still holds
     e_dg, e_w, kappa = out[3.0]
     assert e_w < 2.0 * e_dg and kappa < 4.0
+
+
+def test_sum_condition_on_a_worked_example():
+    """Two tokens, one input column: dW_router = (1, 2) from terms of magnitude (3, 2); db_router the same
+    here; a sum that cancels completely has no finite condition."""
+    x = np.array([[1.0], [1.0]])
+    ds = np.array([[2.0, 1.0], [-1.0, 1.0]])
+    c = sum_condition(x, ds)
+    want = np.sqrt(13.0) / np.sqrt(5.0)
+    assert abs(c["dW_router"] - want) < 1e-12 and abs(c["db_router"] - want) < 1e-12
+    x2 = np.array([[1.0], [-1.0]])                      # signed inputs: dW = (3, 0), magnitudes (3, 2)
+    c2 = sum_condition(x2, ds)
+    assert abs(c2["dW_router"] - np.sqrt(13.0) / 3.0) < 1e-12 and abs(c2["db_router"] - want) < 1e-12
+    assert sum_condition(x, np.array([[1.0, -1.0], [-1.0, 1.0]]))["db_router"] == float("inf")
+
+
+@pytest.mark.parametrize("mode,k", [(O.ROUTE_TOPK_RENORM, 2), (O.ROUTE_SWITCH_TOP1, 1)])
+def test_router_gradients_from_dg_with_the_loss_differentiated_through_u(mode, k):
+    """With L_LB differentiated through u (the mean gate), the oracle adds alpha N p_i / T to the gradient
+    of every gate; router_grads_from_dg swaps only the feed-forward part <dY, FF_e(x)> of dg, so the oracle's
+    own such part must give back its gradients, and the total dg must not (alpha is large here)."""
+    L = synth.make_layer(96, 64, 96, 4, dtype=torch.bfloat16, unit_rms=True, with_dY=True)
+    fwd = run_oracle_forward(L, k, mode, 0.5, O.LB_GATE_MEAN)
+    ref = O.moe_backward(to_np(L["x"]), to_np(L["W_router"]), to_np(L["b_router"]), experts_np(L["W1"]),
+                         experts_np(L["W3"]), experts_np(L["W2"]), k, mode, to_np(L["dY"]), fwd, 0.5, O.LB_GATE_MEAN,
+                         1.0, grad_through_u=True)
+    x = to_np(L["x"])
+    assert rel_err(ref["dg"], ref["dg_ff"])[0] > 1e-3
+    dWr, db = router_grads_from_dg(x, ref["dg_ff"], fwd, ref, mode)
+    np.testing.assert_allclose(dWr, ref["dW_router"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(db, ref["db_router"], rtol=1e-12, atol=1e-15)
+    dWr_wrong, _ = router_grads_from_dg(x, ref["dg"], fwd, ref, mode)
+    assert rel_err(dWr_wrong, ref["dW_router"])[0] > 1e-4

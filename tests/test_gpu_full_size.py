@@ -17,7 +17,7 @@ from paper_2403_07816_amd import binding as B
 from paper_2403_07816_amd import synth
 
 from conftest import assert_close
-from helpers import TOL, check_route, check_router_grads_bf16, to_np
+from helpers import TOL, as_passed, check_route, check_router_grads_bf16, to_np
 
 pytestmark = pytest.mark.gpu
 BF16 = torch.bfloat16
@@ -93,6 +93,7 @@ def check_complete(x, dY, U, Wr, b, W1, W3, W2, k, mode, alpha, lam, tau, fwd, o
 def run_full(L, T, k, mode, alpha, lam, W1, W3, W2, Wr, bias=None, backward=True, n_random=24, n_cols=6, seed=0,
              noise=None, tau=1.0, cf=0.0, complete=True, what=""):
     rng = np.random.default_rng(seed)
+    tau, cf = as_passed(tau), as_passed(cf)
     E, d, f = W1.shape[0], W1.shape[1], W1.shape[2]
     x, dY = L["x"][:T].contiguous(), L["dY"][:T].contiguous()
     U = L["U"][:T].contiguous() if mode == B.BTX_ROUTE_SAMPLE_TOP1 else noise

@@ -200,6 +200,13 @@ def test_bf16_forward_backward(T, d, f, E, k):
     run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True)
 
 
+@pytest.mark.parametrize("T,d,f,E,k", [(313, 120, 264, 4, 2), (200, 264, 520, 3, 1), (150, 72, 776, 5, 3)])
+def test_bf16_off_the_mfma_path_with_wide_experts(T, d, f, E, k):
+    """bf16 shapes that the MFMA kernels do not take (d or f not a multiple of 32) with f > 256: the plain
+    kernels leave one sum of D * act per grouped row, not one per 256 columns as the MFMA path does."""
+    run_layer_and_check(T, d, f, E, k, BF16, unit_rms=True, poison=True)
+
+
 def _random_mfma_case(i):
     rng = np.random.default_rng(1000 + i)
     E = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
@@ -263,6 +270,14 @@ def test_bf16_switch_with_capacity_factor():
     G, r, out, g = run_layer_and_check(900, 256, 256, 4, 1, BF16, mode=B.BTX_ROUTE_SWITCH_TOP1, bias=[2.0, 0, 0, 0],
                                        unit_rms=True, cf=1.5)
     assert int((r.inv_pos < 0).sum()) > 0 and int(r.offsets[1]) == 338   # ceil(1.5 * 900 / 4)
+
+
+def test_capacity_limit_follows_the_float_that_was_passed():
+    """cf = 0.8 reaches the library as the float32 nearest to 0.8, which lies above it: at T/E = 260 the
+    limit is 209 rows, not 208; the oracle is given the same number."""
+    G, r, out, g = run_layer_and_check(1040, 128, 96, 4, 1, F32, mode=B.BTX_ROUTE_SWITCH_TOP1, bias=[1.5, 0, 0, 0],
+                                       cf=0.8)
+    assert int(r.offsets[1]) == 209
 
 
 def test_bf16_top2_with_capacity_factor():

@@ -596,3 +596,12 @@ def test_three_matrix_ff_matches_table4_active_params():
         total = base + O.ff_active_params(4096, 11008, k, 32)
         # both printed numbers are rounded to 0.1, so allow 0.05 + 0.05; a 2-matrix FF would miss by 1.4
         assert abs(total / 1e9 - v) <= 0.1001, (k, total)
+
+
+def test_capacity_is_taken_on_the_number_that_is_passed():
+    """ceil(cf * T*k / E) is sensitive to the last bit of cf when the product is an integer: 0.8 gives
+    208 rows at T*k/E = 260, the float32 nearest to 0.8 (what a C float argument carries) 209."""
+    assert O.capacity(1040, 1, 4, 0.8) == 208
+    assert O.capacity(1040, 1, 4, float(np.float32(0.8))) == 209
+    assert O.capacity(1040, 1, 4, 1.25) == 325 and O.capacity(1041, 1, 4, 1.25) == 326
+    assert O.capacity(16384, 1, 4, 1.5) == 6144 and O.capacity(900, 1, 4, 1.5) == 338
