@@ -356,6 +356,8 @@ int btx_mix_experts(const void* W1, const void* W3, const void* W2, int dtype, i
  *   lowp          DEVICE [numel] bf16, 8-byte aligned, may be NULL: receives the updated
  *                 weights rounded once to bf16 (the copy the layer's GEMMs read)
  *   step          1-based count of updates, for the bias corrections
+ *   lr, beta1, beta2, eps, weight_decay: floats; the arithmetic runs on the float values as
+ *                 passed (1 - 0.999f is 1.3e-5 relative away from 0.001)
  * Errors: BTX_ERR_INVALID_ARG (NULL / misaligned pointers, step < 1, beta outside [0,1),
  * negative eps), BTX_ERR_HIP. */
 int btx_adamw_step(float* master, float* m, float* v, const void* grad, int grad_dtype, void* lowp, int64_t numel,

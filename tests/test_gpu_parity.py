@@ -9,7 +9,7 @@ from paper_2403_07816_amd import binding as B
 from paper_2403_07816_amd import synth
 
 from conftest import assert_close
-from helpers import TOL, run_block_and_check, run_layer_and_check, to_dev, to_np, experts_np, check_route
+from helpers import TOL, as_passed, run_block_and_check, run_layer_and_check, to_dev, to_np, experts_np, check_route
 
 pytestmark = pytest.mark.gpu
 
@@ -514,8 +514,11 @@ def test_block_step_replays_from_a_hip_graph():
 
 # -------------------------------------------------------------------- AdamW
 @pytest.mark.parametrize("gdtype", [F32, BF16])
-@pytest.mark.parametrize("n", [4096 * 33 + 3, 5, 1 << 20])
-def test_adamw_steps_follow_the_oracle(gdtype, n):
+@pytest.mark.parametrize("n,beta2", [(4096 * 33 + 3, 0.95), (5, 0.95), (1 << 20, 0.95), (65537, 0.999)])
+def test_adamw_steps_follow_the_oracle(gdtype, n, beta2):
+    """The hyper-parameters reach the library as C floats; the oracle is given the same numbers
+    (1 - beta2 differs by 1.3e-5 between 0.999 and the float nearest to it)."""
+    lr, beta1, beta2, eps, wd = (as_passed(v) for v in (1e-4, 0.9, beta2, 1e-8, 0.1))
     g = torch.Generator().manual_seed(n)
     p = torch.randn(n, generator=g) * 0.02
     m = torch.zeros(n)
@@ -525,8 +528,8 @@ def test_adamw_steps_follow_the_oracle(gdtype, n):
     po, mo, vo = p.double().numpy(), m.double().numpy(), v.double().numpy()
     for step in range(1, 4):
         grad = (torch.randn(n, generator=g) * 1e-3).to(gdtype)
-        B.btx_adamw_step(P, M, V, grad.cuda(), step, 1e-4, 0.9, 0.95, 1e-8, 0.1, lowp=low)
-        po, mo, vo = O.adamw_step(po, grad.double().numpy(), mo, vo, step, 1e-4, 0.9, 0.95, 1e-8, 0.1)
+        B.btx_adamw_step(P, M, V, grad.cuda(), step, lr, beta1, beta2, eps, wd, lowp=low)
+        po, mo, vo = O.adamw_step(po, grad.double().numpy(), mo, vo, step, lr, beta1, beta2, eps, wd)
     # the update itself (weights move by ~1e-4 per step): compared as a difference from the start
     start = p.double().numpy()
     assert_close(P.cpu().double().numpy() - start, po - start, 1e-4, "update")
