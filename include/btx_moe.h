@@ -24,6 +24,9 @@
  *     Arguments are validated before anything is launched; on an error status
  *     no kernel has been enqueued.
  *   - T == 0 is a valid no-op (BTX_OK).
+ *   - Rows move as 16-byte pieces: every tensor of rows (x, the expert weights and their
+ *     gradients, saved activations, outputs, workspaces) starts on a 16-byte boundary, and
+ *     the expert strides are multiples of 8 elements; BTX_ERR_INVALID_ARG otherwise.
  *   - Every kernel is free of atomics: results are bit-identical run to run.  The order
  *     of every sum is fixed by the shapes, the routing counts and the number of compute
  *     units of the device (the bf16 up-projection, down-projection and input-gradient
@@ -248,7 +251,7 @@ int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, cons
  * dtype BTX_BF16: bf16 storage, bf16 MFMA products, fp32 accumulation; the
  * activation silu(h1)*h3 and the expert output are rounded to bf16 once each.
  * dtype BTX_F32: plain fp32 FMA kernels (parity path, not the fast path).
- * Requirements: d % 8 == 0, f % 8 == 0, strides >= d*f.
+ * Requirements: d % 8 == 0, f % 8 == 0, strides >= d*f and multiples of 8.
  * Limits (BTX_ERR_UNSUPPORTED beyond them; also for btx_moe_ff_backward): the bf16 kernels (d and f
  * multiples of 32, both >= 64) address the padded grouped rows with 32-bit byte offsets,
  * ceil(R/64)*64 + 64*E < 2^23 (about 8.3 M routed rows); the plain kernels (fp32, or bf16 with other

@@ -83,10 +83,11 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-def _ptr(t: Optional[torch.Tensor]):
+def _ptr(t: Optional[torch.Tensor], stacked: bool = False):
+    """Device address of a contiguous tensor (stacked: of expert matrices that _stacked() accepts)."""
     if t is None:
         return None
-    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    assert t.is_cuda and (t.is_contiguous() or (stacked and _stacked(t))), "device-resident contiguous tensors only"
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -204,7 +205,9 @@ def btx_rmsnorm_backward(dXn: torch.Tensor, h: torch.Tensor, gain: torch.Tensor,
 
 
 def _stacked(W: torch.Tensor) -> Tuple[int, int]:
-    assert W.dim() == 3 and W.is_contiguous()
+    """(experts, expert stride in elements) of stacked expert matrices: each [rows, cols] matrix contiguous,
+    the experts any multiple of 8 elements apart."""
+    assert W.dim() == 3 and W.stride(2) == 1 and W.stride(1) == W.shape[2] and W.stride(0) >= W.shape[1] * W.shape[2]
     return W.shape[0], W.stride(0)
 
 
@@ -227,7 +230,7 @@ def btx_moe_ff_forward(x: torch.Tensor, W1: torch.Tensor, W3: torch.Tensor, W2: 
         h1, h3 = saved if saved is not None else (torch.empty((T * k, f), dtype=x.dtype, device=x.device),
                                                   torch.empty((T * k, f), dtype=x.dtype, device=x.device))
     ws = _workspace(lib.btx_moe_ff_forward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
-    st = lib.btx_moe_ff_forward(_ptr(x), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f, E, k,
+    st = lib.btx_moe_ff_forward(_ptr(x), _ptr(W1, True), _ptr(W3, True), _ptr(W2, True), dt, s13, s2, T, d, f, E, k,
                                 _ptr(routing.gates), _ptr(routing.offsets), _ptr(routing.perm), _ptr(routing.inv_pos),
                                 _ptr(residual), _ptr(out), _ptr(h1), _ptr(h3), _ptr(ws), ws.numel(), _stream())
     _check(st, "btx_moe_ff_forward")
@@ -260,18 +263,23 @@ def btx_moe_ff_backward(dY: torch.Tensor, x: torch.Tensor, W_router: torch.Tenso
     dt = _dtype_code(x)
     dW_dtype = x.dtype if dW_dtype is None else dW_dtype
     if out is None:
-        mk = (lambda W: None) if frozen_experts else (lambda W: torch.empty(W.shape, dtype=dW_dtype, device=x.device))
+        # weight gradients are stacked like the weights: same expert strides
+        mk = (lambda W: None) if frozen_experts else (
+            lambda W: torch.empty_strided(W.shape, W.stride(), dtype=dW_dtype, device=x.device))
         out = Grads(torch.empty_like(x), torch.empty((d, W_router.shape[1]), dtype=torch.float32, device=x.device),
                     torch.empty(W_router.shape[1], dtype=torch.float32, device=x.device), mk(W1), mk(W3), mk(W2))
+    for dW, W in ((out.dW1, W1), (out.dW3, W3), (out.dW2, W2)):
+        assert dW is None or (dW.shape == W.shape and _stacked(dW)[1] == _stacked(W)[1]), "dW is stacked like W"
     dwc = BTX_F32 if dW_dtype == torch.float32 else BTX_BF16
     ws = _workspace(lib.btx_moe_ff_backward_workspace_bytes(T, d, f, E, k, dt), x.device, workspace)
-    st = lib.btx_moe_ff_backward(_ptr(dY), _ptr(x), _ptr(W_router), _ptr(W1), _ptr(W3), _ptr(W2), dt, s13, s2, T, d, f,
+    st = lib.btx_moe_ff_backward(_ptr(dY), _ptr(x), _ptr(W_router), _ptr(W1, True), _ptr(W3, True), _ptr(W2, True), dt, s13, s2,
+                                 T, d, f,
                                  E, k, route_mode, lb_mode, lb_alpha, lb_grad_scale, flags, _ptr(noise), tau,
                                  _ptr(routing.topk_idx),
                                  _ptr(routing.gates), _ptr(routing.probs), _ptr(routing.offsets), _ptr(routing.perm),
                                  _ptr(routing.inv_pos), _ptr(routing.gate_sum), _ptr(routing.prob_sum),
                                  _ptr(routing.counts), _ptr(h1), _ptr(h3), _ptr(out.dX), _ptr(out.dW_router),
-                                 _ptr(out.db_router), _ptr(out.dW1), _ptr(out.dW3), _ptr(out.dW2), dwc, _ptr(ws),
+                                 _ptr(out.db_router), _ptr(out.dW1, True), _ptr(out.dW3, True), _ptr(out.dW2, True), dwc, _ptr(ws),
                                  ws.numel(), _stream())
     _check(st, "btx_moe_ff_backward")
     return out

@@ -112,6 +112,10 @@ bool shapes_ok(int T, int d, int f, int E, int k) {
 // valid shapes that the kernels' 32-bit offsets or grid limits cannot take
 bool shapes_supported(int dtype, int T, int d, int f, int E, int k) { return ff_rows_supported(dtype, T * k, d, f, E); }
 
+// The kernels move rows as 16-byte pieces: every tensor of rows must start on a 16-byte boundary (NULL passes:
+// optional arguments), and with d, f multiples of 8 every row then does.
+template <typename... P> bool aligned16(P... p) { return (((uintptr_t)p | ...) & 15) == 0; }
+
 }  // namespace
 
 extern "C" {
@@ -163,6 +167,7 @@ int route_impl(const void* x, int x_dtype, const float* gain, float eps, void* x
   if (!x || !W_router || !topk_idx || !gates || !probs || !counts || !offsets || !perm || !inv_pos || !gate_sum ||
       !prob_sum || !lb_loss || !workspace)
     return BTX_ERR_INVALID_ARG;
+  if (!aligned16(x, xn, gain, workspace)) return BTX_ERR_INVALID_ARG;
   if (workspace_bytes < route_workspace_bytes(T, d, E, k)) return BTX_ERR_WORKSPACE;
   // capacity in double, as the specification of the limit is ceil(cf * T*k / E) over the reals
   const double cap_d = capacity_factor > 0.f ? std::ceil((double)capacity_factor * T * k / E) : 0.0;
@@ -235,6 +240,7 @@ int btx_rmsnorm_backward(const void* dXn, const void* h, const float* gain, cons
   if (!dtype_ok(dtype) || T < 0 || d <= 0 || d % 8 != 0 || d > 16384) return BTX_ERR_INVALID_ARG;
   if (T == 0) return BTX_OK;
   if (!dXn || !h || !gain || !rstd || !dH || !dgain || !workspace) return BTX_ERR_INVALID_ARG;
+  if (!aligned16(dXn, h, gain, dres, dH, dgain, workspace)) return BTX_ERR_INVALID_ARG;
   if (workspace_bytes < rmsnorm_bwd_workspace_bytes(T, d)) return BTX_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   BTX_STAGE(BTX_STAGE_NORM_BWD, launch_rmsnorm_bwd(dXn, h, gain, rstd, dres, dtype, T, d, dH, dgain, workspace, s));
@@ -257,6 +263,8 @@ int btx_moe_ff_forward(const void* x, const void* W1, const void* W3, const void
   if (T == 0) return BTX_OK;
   if (!shapes_supported(dtype, T, d, f, E, k)) return BTX_ERR_UNSUPPORTED;
   if (!x || !W1 || !W3 || !W2 || !gates || !offsets || !perm || !inv_pos || !out || !workspace)
+    return BTX_ERR_INVALID_ARG;
+  if (!aligned16(x, W1, W3, W2, residual, out, save_h1, save_h3, workspace) || w13_expert_stride % 8 || w2_expert_stride % 8)
     return BTX_ERR_INVALID_ARG;
   const FwdWs w = carve_forward(workspace, T, d, f, k, dtype, save_h1 != nullptr);
   if (workspace_bytes < w.bytes) return BTX_ERR_WORKSPACE;
@@ -304,6 +312,9 @@ int btx_moe_ff_backward(const void* dY, const void* x, const float* W_router, co
   if (!shapes_supported(dtype, T, d, f, E, k)) return BTX_ERR_UNSUPPORTED;
   if (!dY || !x || !W_router || !W1 || !W3 || !W2 || !topk_idx || !gates || !probs || !offsets || !perm || !inv_pos ||
       !gate_sum || !prob_sum || !counts || !save_h1 || !save_h3 || !dX || !dW_router || !workspace)
+    return BTX_ERR_INVALID_ARG;
+  if (!aligned16(dY, x, W1, W3, W2, save_h1, save_h3, dX, dW1, dW3, dW2, workspace) || w13_expert_stride % 8 ||
+      w2_expert_stride % 8)
     return BTX_ERR_INVALID_ARG;
   const BwdWs w = carve_backward(workspace, T, d, f, E, k, dtype);
   if (workspace_bytes < w.bytes) return BTX_ERR_WORKSPACE;

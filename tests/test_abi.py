@@ -64,6 +64,7 @@ def test_route_rejects_bad_arguments(lib):
     assert route(cf=-0.5) == 1             # capacity factor: 0 (none) or positive
     assert route(dtype=7) == 1
     assert route(x=null) == 1
+    assert route(x=ctypes.c_void_p(264)) == 1      # rows move as 16-byte pieces: 16-byte aligned tensors
     assert route(ws_bytes=16) == 3         # workspace too small
     assert route(T=0) == 0                 # empty batch: nothing to do
     assert route(T=-1) == 1
@@ -73,11 +74,14 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
     p = ctypes.c_void_p(256)
     null = None
 
-    def fwd(T=8, d=64, f=64, E=4, k=2, s13=64 * 64, s2=64 * 64, h1=p, h3=p, ws=1 << 30, out=p):
-        return lib.btx_moe_ff_forward(p, p, p, p, 0, s13, s2, T, d, f, E, k, p, p, p, p, null, out, h1, h3, p, ws, null)
+    def fwd(T=8, d=64, f=64, E=4, k=2, s13=64 * 64, s2=64 * 64, h1=p, h3=p, ws=1 << 30, out=p, x=p, W2=p):
+        return lib.btx_moe_ff_forward(x, p, p, W2, 0, s13, s2, T, d, f, E, k, p, p, p, p, null, out, h1, h3, p, ws, null)
 
     assert fwd(f=12) == 1
     assert fwd(s13=10) == 1                # expert stride smaller than one expert
+    assert fwd(s13=64 * 64 + 4) == 1       # ... or one that puts an expert off the 16-byte grid
+    assert fwd(s2=64 * 64 + 8, ws=0) == 3  # a padded stride on the grid is fine (the call gets as far as the workspace)
+    assert fwd(x=ctypes.c_void_p(264)) == 1 and fwd(W2=ctypes.c_void_p(258)) == 1 and fwd(out=ctypes.c_void_p(8)) == 1
     assert fwd(h3=null) == 1               # h1/h3 come as a pair
     assert fwd(out=null) == 1
     assert fwd(ws=0) == 3
@@ -90,6 +94,7 @@ def test_forward_backward_and_merge_reject_bad_arguments(lib):
                                        p, ws, null)
 
     assert bwd(dW=(p, null, p)) == 1       # weight gradients: all three or none
+    assert bwd(dW=(p, p, ctypes.c_void_p(264))) == 1   # misaligned
     assert bwd(flags=1, lb=0) == 1         # gradient through u only in gate-mean mode
     assert bwd(flags=8) == 1
     assert bwd(dt=0, dwt=1) == 1           # fp32 layer cannot return bf16 weight gradients

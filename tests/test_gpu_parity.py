@@ -171,6 +171,41 @@ def test_results_are_bit_identical_run_to_run():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("dtype,d,f", [(BF16, 128, 160), (BF16, 72, 264), (F32, 64, 176)])
+def test_expert_matrices_with_padding_between_them(dtype, d, f):
+    """Stacked expert weights whose experts lie further apart than d*f elements (the strides are arguments of
+    the C ABI), gradients returned with the same strides: bit for bit what the packed tensors give, and the
+    padding is left alone."""
+    T, E, k, pad = 300, 3, 2, 24
+    L = synth.make_layer(T, d, f, E, dtype=dtype, unit_rms=(dtype == BF16), with_dY=True)
+    G = to_dev(L)
+
+    def padded(W, fill):
+        base = torch.full((E, W.shape[1] * W.shape[2] + pad), fill, dtype=W.dtype, device="cuda")
+        view = base[:, :W.shape[1] * W.shape[2]].view(E, W.shape[1], W.shape[2])
+        return base, view
+    P = {}
+    for n in ("W1", "W3", "W2"):
+        base, view = padded(G[n], float("nan"))
+        view.copy_(G[n])
+        P[n] = view
+    r = B.btx_moe_route(G["x"], G["W_router"], None, None, k, lb_alpha=0.01)
+    out0, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r)
+    out1, g1, g3 = B.btx_moe_ff_forward(G["x"], P["W1"], P["W3"], P["W2"], r)
+    assert torch.equal(out0, out1) and torch.equal(h1, g1) and torch.equal(h3, g3)
+    want = B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, lb_alpha=0.01,
+                                 lb_grad_scale=1.0)
+    bases, views = zip(*(padded(G[n], 7.0) for n in ("W1", "W3", "W2")))
+    got = B.Grads(torch.empty_like(G["x"]), torch.empty_like(want.dW_router), torch.empty_like(want.db_router), *views)
+    B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], P["W1"], P["W3"], P["W2"], r, h1, h3, lb_alpha=0.01,
+                          lb_grad_scale=1.0, out=got)
+    assert torch.equal(got.dX, want.dX) and torch.equal(got.dW_router, want.dW_router)
+    for a, b in ((got.dW1, want.dW1), (got.dW3, want.dW3), (got.dW2, want.dW2)):
+        assert torch.equal(a, b)
+    for base, W in zip(bases, (G["W1"], G["W3"], G["W2"])):
+        assert bool((base[:, W.shape[1] * W.shape[2]:] == 7.0).all())
+
+
 def test_frozen_experts_skip_weight_gradients():
     L = to_dev(synth.make_layer(200, 64, 96, 4, dtype=F32, with_dY=True))
     r = B.btx_moe_route(L["x"], L["W_router"], None, None, 2)
