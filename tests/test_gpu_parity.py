@@ -131,6 +131,29 @@ def test_residual_is_added_in_the_combine(dtype):
     assert lost.any() and torch.equal(out.cpu()[torch.from_numpy(lost)], res[torch.from_numpy(lost)])
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_residual_may_be_x_or_the_output_buffer_and_db_router_may_be_left_out(dtype):
+    """The aliasing the header allows: residual = x (h + FF(h) with h both routed and added) and
+    residual = out (the sum lands on top of the residual), each bit for bit what separate buffers give;
+    db_router = NULL leaves every other gradient as it is."""
+    T, d, f, E, k = 257, 128, 192, 4, 2
+    L = synth.make_layer(T, d, f, E, dtype=dtype, unit_rms=True, with_dY=True)
+    G = to_dev(L)
+    r = B.btx_moe_route(G["x"], G["W_router"], None, None, k)
+    want, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, residual=G["x"].clone())
+    same_x, _, _ = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, residual=G["x"])
+    assert torch.equal(same_x, want)
+    buf = G["x"].clone()
+    B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r, out=buf, residual=buf)
+    assert torch.equal(buf, want)
+    full = B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3)
+    part = B.Grads(torch.empty_like(full.dX), torch.empty_like(full.dW_router), None, torch.empty_like(full.dW1),
+                   torch.empty_like(full.dW3), torch.empty_like(full.dW2))
+    B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, out=part)
+    for a, b in ((part.dX, full.dX), (part.dW_router, full.dW_router), (part.dW1, full.dW1), (part.dW2, full.dW2)):
+        assert torch.equal(a, b)
+
+
 def test_expert_without_tokens_fp32():
     """A strongly negative bias starves expert 2: empty group, zero weight gradients."""
     G, r, out, g = run_layer_and_check(300, 64, 80, 4, 2, F32, bias=[0, 0, -60.0, 0])
