@@ -479,6 +479,37 @@ def test_split_and_blend_match_the_oracle_bit_for_bit(dtype, N, d, f, C):
     assert torch.equal(b1, W1) and torch.equal(b3, W3) and torch.equal(b2, W2)
 
 
+def test_two_layers_on_two_streams_do_not_disturb_each_other():
+    """Nothing in the library is shared between calls but what the caller passes: two layers of different
+    shapes enqueued alternately on two streams (default priority) give, bit for bit, what each gives alone."""
+    cases = [(700, 256, 384, 4, 2), (512, 128, 2048, 3, 1)]
+    layers, alone = [], []
+    for (T, d, f, E, k) in cases:
+        G = to_dev(synth.make_layer(T, d, f, E, dtype=BF16, unit_rms=True, with_dY=True, seed=synth.BASE_SEED + d))
+        mode = B.BTX_ROUTE_TOPK_RENORM if k > 1 else B.BTX_ROUTE_SWITCH_TOP1
+        r = B.btx_moe_route(G["x"], G["W_router"], None, None, k, mode, lb_alpha=0.01)
+        out, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r)
+        g = B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, mode,
+                                  lb_alpha=0.01, lb_grad_scale=1.0)
+        layers.append((G, k, mode))
+        alone.append((r, out, g))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    both = [None, None]
+    for rep in range(3):
+        for i, (G, k, mode) in enumerate(layers):
+            with torch.cuda.stream(streams[i]):
+                r = B.btx_moe_route(G["x"], G["W_router"], None, None, k, mode, lb_alpha=0.01)
+                out, h1, h3 = B.btx_moe_ff_forward(G["x"], G["W1"], G["W3"], G["W2"], r)
+                g = B.btx_moe_ff_backward(G["dY"], G["x"], G["W_router"], G["W1"], G["W3"], G["W2"], r, h1, h3, mode,
+                                          lb_alpha=0.01, lb_grad_scale=1.0)
+                both[i] = (r, out, g)
+    torch.cuda.synchronize()
+    for (r0, out0, g0), (r1, out1, g1) in zip(alone, both):
+        assert torch.equal(r0.perm, r1.perm) and torch.equal(out0, out1) and torch.equal(g0.dX, g1.dX)
+        assert torch.equal(g0.dW1, g1.dW1) and torch.equal(g0.dW2, g1.dW2) and torch.equal(g0.dW_router, g1.dW_router)
+
+
 def test_layer_step_replays_from_a_hip_graph():
     """The three entry points only enqueue kernels on the given stream (no allocation, no
     synchronisation, no memset nodes), so a whole step can be captured once and replayed.
